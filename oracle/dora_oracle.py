@@ -1,0 +1,229 @@
+"""CPU oracle for the DoRA module hot path (float64, numpy).
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, literal statement of what the
+HIP library must compute.  Only the tests, the smoke entry and the bench's
+`cpu_baseline` leg may call it; the product path never does.  It shares no code,
+table or helper with the HIP path and imports nothing from it.
+
+Every function takes float64 arrays (the callers widen the stored, already
+rounded bf16/fp32 inputs exactly) and returns float64.
+
+What is defined here, and from where:
+
+* `composed_weight`, `dense_row_norm`  - Eq. (1): the row norm of W + s B A,
+  written out by forming the dense [d_out, d_in] matrix.  This is the plain
+  definition that the factored form of Sec. 2 reaches up to rounding order.
+* `mag_scale`                          - Eq. (6): g = m / max(w_norm, eps).
+* `adapted_weight`                     - Eq. (1): W' = m * (W + sBA) / ||.||_row.
+* `forward`                            - App. A item 1 (compose equation) with
+  base = x W^T, lora = (x A^T) B^T, inner = s*lora + base (Sec. 4, Tier 1),
+  delta = (g-1)*base + g*(s*lora), Y = base + delta.
+* `backward` / `grad_*`                - Sec. 3.2 and App. C item 2: gradients of
+  the compose, chained through the three linear maps, with the norm held
+  constant (Sec. 2.2 last paragraph; App. A item 2 "detached").
+* `factored_norm_terms`, `assemble_norm` - Algorithm 1 and Eq. (2)-(5), step by
+  step in the paper's order.  Not used to judge the HIP norm (the dense
+  definition is); kept so the three terms can be checked one by one and so the
+  identity itself is pinned against the dense form.
+
+Pins (tests/test_oracle_pins.py): B=0 / s=0 special cases, the r=1 closed form,
+orthonormal-A and W=0 cases, homogeneity, Cauchy-Schwarz on the cross term,
+Y == x W'^T through Eq. (1), hand-worked 2x2 values, central finite differences
+for every gradient (and the negative control with the norm re-evaluated), and a
+loop-by-loop C transcription of the same definitions (oracle/literal.c).
+"""
+from __future__ import annotations
+
+from typing import Dict, Optional
+
+import numpy as np
+
+F64 = np.float64
+
+
+def _f64(a) -> np.ndarray:
+    a = np.asarray(a)
+    if a.dtype != F64:
+        raise TypeError("oracle functions take float64 arrays; widen the stored inputs first")
+    return a
+
+
+# --------------------------------------------------------------------------- norm (Eq. 1)
+
+def composed_weight(W, A, B, s) -> np.ndarray:
+    """D = W + s * (B @ A), the dense [d_out, d_in] composed weight of Eq. (1)."""
+    W, A, B = _f64(W), _f64(A), _f64(B)
+    return W + F64(s) * (B @ A)
+
+
+def dense_row_norm(W, A, B, s) -> np.ndarray:
+    """c[j] = sqrt(sum_k D[j,k]^2): the denominator of Eq. (1), one value per output row."""
+    D = composed_weight(W, A, B, s)
+    return np.sqrt(np.sum(D * D, axis=1))
+
+
+def mag_scale(m, c, eps) -> np.ndarray:
+    """Eq. (6): g = m / max(c, eps)."""
+    return _f64(m) / np.maximum(_f64(c), F64(eps))
+
+
+def adapted_weight(W, A, B, m, s, eps) -> np.ndarray:
+    """Eq. (1): W' = m (.) (W + sBA) / ||W + sBA||_row (with the eps guard of Eq. 6)."""
+    D = composed_weight(W, A, B, s)
+    c = np.sqrt(np.sum(D * D, axis=1))
+    return mag_scale(m, c, eps)[:, None] * D
+
+
+# --------------------------------------------------------------------------- forward
+
+def forward(x, W, A, B, m, s, eps, c: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
+    """Whole forward of one module.
+
+    base  = x W^T                  [T, d_out]
+    h     = x A^T                  [T, r]
+    lora  = h B^T                  [T, d_out]
+    inner = s*lora + base          (the tensor Tier 1 saves for backward)
+    delta = (g-1)*base + g*(s*lora)   (compose equation, App. A item 1)
+    y     = base + delta           (what the caller of the module ends up with)
+    """
+    x, W, A, B, m = _f64(x), _f64(W), _f64(A), _f64(B), _f64(m)
+    s = F64(s)
+    if c is None:
+        c = dense_row_norm(W, A, B, s)
+    g = mag_scale(m, c, eps)
+    base = x @ W.T
+    h = x @ A.T
+    lora = h @ B.T
+    inner = s * lora + base
+    delta = (g - 1.0)[None, :] * base + g[None, :] * (s * lora)
+    y = base + delta
+    return {"c": c, "g": g, "base": base, "h": h, "lora": lora, "inner": inner, "delta": delta, "y": y}
+
+
+def compose_delta(base, lora, g, s) -> np.ndarray:
+    """App. C item 1: delta = (g-1) (.) base + g (.) s (.) lora, g broadcast along the last axis."""
+    base, lora, g = _f64(base), _f64(lora), _f64(g)
+    return (g - 1.0)[None, :] * base + g[None, :] * (F64(s) * lora)
+
+
+# --------------------------------------------------------------------------- backward (norm detached)
+
+def grad_compose(dy, inner, g, c, s, eps):
+    """Sec. 3.2 / App. C item 2, for upstream gradient dy of y = base + delta.
+
+    d_lora = g*s*dy ; d_base (through delta) = (g-1)*dy, plus the identity path
+    of y = base + delta gives dy, so base receives g*dy in total;
+    d_mag[j] = sum_t dy[t,j]*inner[t,j] is the gradient w.r.t. g, and since
+    g = m / max(c, eps) with c constant, dm = d_mag / max(c, eps).
+    """
+    dy, inner, g, c = _f64(dy), _f64(inner), _f64(g), _f64(c)
+    d_lora = g[None, :] * F64(s) * dy
+    d_base_total = dy + (g - 1.0)[None, :] * dy
+    d_mag = np.sum(dy * inner, axis=0)
+    dm = d_mag / np.maximum(c, F64(eps))
+    return d_lora, d_base_total, dm
+
+
+def grad_m(dy, x, W, A, B, m, s, eps, c=None) -> np.ndarray:
+    f = forward(x, W, A, B, m, s, eps, c)
+    return grad_compose(_f64(dy), f["inner"], f["g"], f["c"], s, eps)[2]
+
+
+def grad_B(dy, x, W, A, B, m, s, eps, c=None) -> np.ndarray:
+    """lora = h B^T  =>  dB = d_lora^T h, with h = x A^T."""
+    x, W, A, B, m, dy = _f64(x), _f64(W), _f64(A), _f64(B), _f64(m), _f64(dy)
+    if c is None:
+        c = dense_row_norm(W, A, B, s)
+    g = mag_scale(m, c, eps)
+    d_lora = g[None, :] * F64(s) * dy
+    h = x @ A.T
+    return d_lora.T @ h
+
+
+def grad_A(dy, x, W, A, B, m, s, eps, c=None) -> np.ndarray:
+    """h = x A^T, lora = h B^T  =>  dh = d_lora B, dA = dh^T x."""
+    x, W, A, B, m, dy = _f64(x), _f64(W), _f64(A), _f64(B), _f64(m), _f64(dy)
+    if c is None:
+        c = dense_row_norm(W, A, B, s)
+    g = mag_scale(m, c, eps)
+    d_lora = g[None, :] * F64(s) * dy
+    dh = d_lora @ B
+    return dh.T @ x
+
+
+def grad_x(dy, x, W, A, B, m, s, eps, c=None) -> np.ndarray:
+    """base = x W^T and h = x A^T both depend on x: dx = d_base W + dh A."""
+    x, W, A, B, m, dy = _f64(x), _f64(W), _f64(A), _f64(B), _f64(m), _f64(dy)
+    if c is None:
+        c = dense_row_norm(W, A, B, s)
+    g = mag_scale(m, c, eps)
+    d_lora = g[None, :] * F64(s) * dy
+    d_base = dy + (g - 1.0)[None, :] * dy
+    dh = d_lora @ B
+    return d_base @ W + dh @ A
+
+
+def backward(dy, x, W, A, B, m, s, eps, c=None) -> Dict[str, np.ndarray]:
+    """All four gradients (W is frozen and gets none)."""
+    if c is None:
+        c = dense_row_norm(_f64(W), _f64(A), _f64(B), s)
+    return {
+        "dx": grad_x(dy, x, W, A, B, m, s, eps, c),
+        "dA": grad_A(dy, x, W, A, B, m, s, eps, c),
+        "dB": grad_B(dy, x, W, A, B, m, s, eps, c),
+        "dm": grad_m(dy, x, W, A, B, m, s, eps, c),
+    }
+
+
+# --------------------------------------------------------------------------- Algorithm 1 (factored form)
+
+def factored_norm_terms(W, A, B, chunk: Optional[int] = None) -> Dict[str, np.ndarray]:
+    """Algorithm 1, the loop over d_in chunks, in the paper's order.
+
+    Returns base_sq [d_out], cross [d_out], G [r, r] and ba_sq [d_out].
+    """
+    W, A, B = _f64(W), _f64(A), _f64(B)
+    d_out, d_in = W.shape
+    r = A.shape[0]
+    cs = d_in if chunk is None else int(chunk)
+    base_sq = np.zeros(d_out, F64)
+    cross = np.zeros(d_out, F64)
+    G = np.zeros((r, r), F64)
+    for c0 in range(0, d_in, cs):
+        W_c = W[:, c0:c0 + cs]
+        A_c = A[:, c0:c0 + cs]
+        base_sq += np.sum(W_c ** 2, axis=1)
+        G += A_c @ A_c.T
+        U_c = W_c @ A_c.T
+        cross += np.sum(B * U_c, axis=1)
+    ba_sq = np.sum((B @ G) * B, axis=1)
+    return {"base_sq": base_sq, "cross": cross, "G": G, "ba_sq": ba_sq}
+
+
+def assemble_norm(base_sq, cross, ba_sq, s) -> np.ndarray:
+    """Eq. (5): sqrt(max(base_sq + 2s*cross + s^2*ba_sq, 0)); a NaN radicand stays NaN."""
+    s = F64(s)
+    rad = _f64(base_sq) + (2.0 * s) * _f64(cross) + (s * s) * _f64(ba_sq)
+    rad = np.where(rad < 0.0, 0.0, rad)  # NaN < 0 is False, so NaN passes through
+    return np.sqrt(rad)
+
+
+def factored_row_norm(W, A, B, s, chunk: Optional[int] = None) -> np.ndarray:
+    if F64(s) == 0.0:  # scale-is-zero fast path of Algorithm 1's notes
+        W = _f64(W)
+        return np.sqrt(np.sum(W * W, axis=1))
+    t = factored_norm_terms(W, A, B, chunk)
+    return assemble_norm(t["base_sq"], t["cross"], t["ba_sq"], s)
+
+
+def chunk_size(budget_bytes: int, d_out: int, d_in: int) -> int:
+    """Algorithm 1's chunk rule: min(d_in, floor(budget / (4 d_out))) aligned down to 64."""
+    cs = min(d_in, budget_bytes // (4 * d_out))
+    if cs < d_in:
+        cs = max(64, (cs // 64) * 64)
+    return int(cs)
+
+
+def theory_memory_ratio(d_out: int, d_in: int, r: int) -> float:
+    """Table 1 / Table 5 'theory' column: dense [d_out,d_in] over U[d_out,r] + G[r,r]."""
+    return (d_out * d_in) / float(d_out * r + r * r)
