@@ -1,0 +1,188 @@
+/*
+ * libdora - the DoRA adapter hot path on one MI355X (gfx950), C ABI.
+ *
+ * One adapted linear module:  W [d_out, d_in] frozen, A [r, d_in], B [d_out, r],
+ * magnitude m [d_out], scaling s; activations x [tokens, d_in]  (Sec. 1, Eq. 1).
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  Row-major,
+ *     contiguous, 16-byte aligned.  Inputs are const and never modified.
+ *   - `dtype` selects the storage type of W, A, B, x, y, dy, dx, saved_h,
+ *     saved_inner, base, lora: DORA_BF16 (bfloat16) or DORA_F32.  Accumulation is
+ *     always fp32.  w_norm, m, g, gm1, dm, dA, dB are fp32 for either dtype.
+ *   - Shape limits: d_out, d_in multiples of 8; r a multiple of 8 (bf16) or >= 1
+ *     (fp32: d_out, d_in, r multiples of 4); tokens >= 0 (0 is a no-op that still
+ *     computes weight-only results); every tensor below 2^31 elements.
+ *   - `ws` is caller-provided scratch of at least dora_workspace_bytes(desc,
+ *     phase) bytes, 256-byte aligned.  The library allocates no device memory,
+ *     keeps no state between calls, enqueues everything on `stream` (a
+ *     hipStream_t passed as void*; NULL is the default stream) and returns
+ *     without synchronising.  Results are deterministic run to run (no
+ *     floating-point atomics anywhere).
+ *   - Errors are returned, never thrown; on error nothing has been enqueued
+ *     unless the status is DORA_ERR_HIP.
+ */
+#ifndef DORA_H
+#define DORA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { DORA_F32 = 0, DORA_BF16 = 1 } dora_dtype;
+
+typedef enum {
+    DORA_OK = 0,
+    DORA_ERR_NULL = 1,      /* a required pointer is NULL */
+    DORA_ERR_SHAPE = 2,     /* a dimension is negative, too large or violates the multiple-of rule */
+    DORA_ERR_ALIGN = 3,     /* a pointer is not 16-byte aligned (ws: 256) */
+    DORA_ERR_DTYPE = 4,     /* unknown dtype */
+    DORA_ERR_WORKSPACE = 5, /* ws_bytes < dora_workspace_bytes */
+    DORA_ERR_HIP = 6        /* a HIP runtime call failed (launch error) */
+} dora_status;
+
+typedef struct {
+    int64_t d_out, d_in, r, tokens;
+    int32_t dtype; /* dora_dtype */
+    float s;       /* LoRA scaling, e.g. rsLoRA alpha / sqrt(r) */
+    float eps;     /* guard of Eq. 6; <= 0 selects the default of App. A item 2: 1e-12 (F32), 1e-6 (BF16) */
+} dora_desc;
+
+typedef enum {
+    DORA_PHASE_NORM = 0,              /* dora_norm */
+    DORA_PHASE_FORWARD = 1,           /* dora_forward with w_norm == NULL and saved_inner == NULL (worst case) */
+    DORA_PHASE_BACKWARD = 2,          /* dora_backward with saved_h / saved_inner given */
+    DORA_PHASE_BACKWARD_RECOMPUTE = 3,/* dora_backward with saved_* == NULL (recomputes h and inner) */
+    DORA_PHASE_COMPOSE_BACKWARD = 4   /* dora_compose_backward */
+} dora_phase;
+
+/* Scratch bytes an entry point needs for this shape.  Returns 0 for an invalid desc. */
+size_t dora_workspace_bytes(const dora_desc* desc, int phase);
+
+/*
+ * Row-wise norm of the composed weight, w_norm[j] = || W[j,:] + s (B A)[j,:] ||_2, by the
+ * factored form of Sec. 2 (Eq. 2-5, Algorithm 1): base_sq + 2s*cross + s^2*ba_sq, with
+ * U = W A^T and G = A A^T accumulated in fp32 and never written as dense [d_out, d_in]
+ * data.  s == 0 skips the cross and Gram terms (Algorithm 1, notes).  Negative radicands
+ * clamp to 0, NaN propagates (App. C item 3).
+ *   W, A, B : device, const, `dtype`.   w_norm : device, out, fp32 [d_out].
+ */
+dora_status dora_norm(const dora_desc* desc, const void* W, const void* A, const void* B,
+                      float* w_norm, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Magnitude scale of Eq. 6: g = m / max(w_norm, eps), and the explicit small
+ * correction gm1 = g - 1 of Sec. 3.1, formed as (m - cc)/cc with cc = max(w_norm, eps)
+ * so that it does not suffer the rounding of g.  g or gm1 may be NULL (not both).
+ */
+dora_status dora_mag_scale(const dora_desc* desc, const float* m, const float* w_norm,
+                           float* g, float* gm1, void* stream);
+
+/*
+ * Compose pass of Sec. 3.1 / App. C item 1 on existing activations:
+ *   delta = gm1 (.) base + g (.) (s * lora)         (fp32 arithmetic, one rounding at the store)
+ *   out   = write_delta ? delta : base + delta
+ *   inner = s * lora + base                          (only if inner != NULL; Sec. 4, Tier 1)
+ * base, lora : device, const, `dtype`, [tokens, d_out].  g : fp32 [d_out].  gm1 : fp32 [d_out]
+ * or NULL (then g - 1 is formed in fp32).  out / inner : device, `dtype`, [tokens, d_out];
+ * out may alias base and inner may alias lora (element-wise in place); other overlaps are
+ * not allowed.  Needs no workspace.  d_in and r of desc are ignored.
+ */
+dora_status dora_compose(const dora_desc* desc, const void* base, const void* lora,
+                         const float* g, const float* gm1,
+                         void* out, int write_delta, void* inner, void* stream);
+
+/*
+ * Backward of the compose (Sec. 3.2, App. C item 2), for the upstream gradient dy of
+ * y = base + delta:
+ *   dz = g (.) dy      (gradient reaching base; the gradient reaching lora is s * dz)
+ *   dm[j] = ( sum_t dy[t,j] * inner[t,j] ) / max(w_norm[j], eps)
+ * The column sum is a two-stage, fixed-order reduction fused into the same pass (Sec. 7,
+ * "LLM-guided optimization"), no atomics.  dm == NULL (frozen magnitude) skips it and then
+ * inner and w_norm may be NULL.   dy, inner : const `dtype` [tokens, d_out];  dz : `dtype`.
+ */
+dora_status dora_compose_backward(const dora_desc* desc, const void* dy, const void* inner,
+                                  const float* g, const float* w_norm,
+                                  void* dz, float* dm, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * The three forward contractions on their own (App. A item 1): base = x W^T [tokens, d_out],
+ * h = x A^T [tokens, r], lora = h B^T [tokens, d_out], each rounded once to `dtype`.
+ * Exactly the launches dora_forward makes for these steps.  Needs no workspace.
+ */
+dora_status dora_project(const dora_desc* desc, const void* x, const void* W, const void* A, const void* B,
+                         void* base, void* h, void* lora, void* stream);
+
+/*
+ * Whole forward of the module (App. A item 1): norm (unless w_norm is given), g,
+ * base = x W^T, h = x A^T, lora = h B^T, compose;  y = base + delta = g (.) (base + s*lora).
+ *   x [tokens, d_in], W, A, B : const `dtype`.   m : const fp32 [d_out].
+ *   w_norm : const fp32 [d_out] or NULL (NULL: computed here into the workspace).
+ *   y : out `dtype` [tokens, d_out].
+ *   saved_h : out `dtype` [tokens, r] or NULL.   saved_inner : out `dtype` [tokens, d_out] or NULL.
+ *   w_norm_out : out fp32 [d_out] or NULL (receives the norm used, for the backward call).
+ */
+dora_status dora_forward(const dora_desc* desc, const void* x, const void* W, const void* A,
+                         const void* B, const float* m, const float* w_norm,
+                         void* y, void* saved_h, void* saved_inner, float* w_norm_out,
+                         void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Backward of the module with the norm held constant (Sec. 2.2; App. A item 2) and W frozen:
+ *   dz = g (.) dy;  dh = s * dz B;  dx = dz W + dh A;  dA = dh^T x;  dB = s * dz^T h;
+ *   dm as in dora_compose_backward.
+ *   dy [tokens, d_out], x, W, A, B : const `dtype`.  m : const fp32.
+ *   w_norm : const fp32 [d_out] or NULL (NULL: recomputed).
+ *   saved_h / saved_inner : const `dtype` as written by dora_forward, or NULL (recomputed
+ *   here - the gradient-checkpointing pattern).
+ *   dx : out `dtype` [tokens, d_in].  dA : out fp32 [r, d_in].  dB : out fp32 [d_out, r].
+ *   dm : out fp32 [d_out] or NULL (frozen magnitude).  Any of dx, dA, dB may be NULL to skip it.
+ */
+dora_status dora_backward(const dora_desc* desc, const void* dy, const void* x, const void* W,
+                          const void* A, const void* B, const float* m, const float* w_norm,
+                          const void* saved_h, const void* saved_inner,
+                          void* dx, float* dA, float* dB, float* dm,
+                          void* ws, size_t ws_bytes, void* stream);
+
+const char* dora_status_str(int status);
+
+/*
+ * Per-kernel timing for measurement harnesses (not part of the method).  While enabled, every
+ * kernel launch made by the entry points above is bracketed by a pair of HIP events recorded on
+ * the launch stream.  dora_trace_collect synchronises those events and adds each launch's
+ * duration to its kernel's slot; dora_trace_get reads one slot.  Kernel ids are the
+ * DORA_K_* values; dora_trace_name returns a short label.  Enabling tracing creates host-side
+ * event objects only (no device memory).  Not thread-safe.
+ */
+enum {
+    DORA_K_NORM_CROSS = 0,   /* U = W A^T tile + base_sq + rowdot(B, U) partials      */
+    DORA_K_GRAM = 1,         /* G = A A^T split-K partials                             */
+    DORA_K_GRAM_REDUCE = 2,  /* fixed-order sum of Gram partials, hi/lo split          */
+    DORA_K_BA_SQ = 3,        /* rowdot(B, B G) partials                                */
+    DORA_K_NORM_FINAL = 4,   /* Eq. 5 assembly                                         */
+    DORA_K_MAG_SCALE = 5,    /* Eq. 6                                                  */
+    DORA_K_GEMM_BASE = 6,    /* base = x W^T                                           */
+    DORA_K_GEMM_H = 7,       /* h = x A^T                                              */
+    DORA_K_GEMM_LORA = 8,    /* lora = h B^T                                           */
+    DORA_K_COMPOSE_FWD = 9,
+    DORA_K_COMPOSE_BWD = 10,
+    DORA_K_DM_FINAL = 11,    /* second stage of the dm column reduction                */
+    DORA_K_GEMM_DH = 12,     /* dh = s dz B                                            */
+    DORA_K_GEMM_DX = 13,     /* dx = dz W + dh A                                       */
+    DORA_K_GEMM_DA = 14,     /* dA = dh^T x                                            */
+    DORA_K_GEMM_DB = 15,     /* dB = s dz^T h                                          */
+    DORA_K_COUNT = 16
+};
+void dora_trace_enable(int on);
+void dora_trace_reset(void);
+int dora_trace_collect(void); /* returns a dora_status */
+int dora_trace_get(int kernel_id, double* total_ms, int64_t* launches);
+const char* dora_trace_name(int kernel_id);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DORA_H */

@@ -1,0 +1,116 @@
+// Shared declarations of the HIP translation units of libdora (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/dora.h"
+
+namespace dora {
+
+typedef uint16_t bf16_t;  // storage only; arithmetic is fp32
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+// ---- bf16 <-> fp32 on the device ------------------------------------------------------------
+__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+
+// round-to-nearest-even, NaN kept quiet
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    uint32_t r = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    return (f != f) ? 0x7fc0u : r;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+
+// ---- kernel timing hook (see dora_trace_* in dora.h) ------------------------------------------
+void trace_begin(int kernel_id, hipStream_t stream);
+void trace_end(int kernel_id, hipStream_t stream);
+
+struct TraceScope {
+    int id;
+    hipStream_t st;
+    TraceScope(int kernel_id, hipStream_t stream) : id(kernel_id), st(stream) { trace_begin(id, st); }
+    ~TraceScope() { trace_end(id, st); }
+};
+
+// ---- bf16 MFMA GEMM family ---------------------------------------------------------------------
+// C[M,N] = alpha * sum over segments of  Aop[m,k] * Bop[n,k]
+// An operand is either K-contiguous (row-major [rows, K], ld = row stride) or K-strided
+// (row-major [K, rows], ld = stride between consecutive k).
+enum GemmEpilogue {
+    EPI_STORE_BF16 = 0,  // C bf16 [M, ldc]
+    EPI_STORE_F32 = 1,   // C fp32 [M, ldc]; with ksplit > 1 slice z goes to C + z*M*ldc
+    EPI_ROWDOT = 2       // no C; partial[z*tiles_n + tn][m] = sum_n acc[m,n] * R[m,n]  (+ base_sq of Aop rows)
+};
+
+struct GemmSeg {
+    const bf16_t* a;
+    const bf16_t* b;
+    int64_t lda, ldb;
+    int K;
+};
+
+struct GemmArgs {
+    GemmSeg seg[2];
+    int nseg;
+    int M, N;
+    int a_kcontig, b_kcontig;  // layout of the M-side / N-side operand (both segments)
+    int epilogue;
+    float alpha;
+    void* c;
+    int64_t ldc;
+    int ksplit;                // split of segment 0's K range (nseg must be 1 when > 1)
+    // EPI_ROWDOT only
+    const bf16_t* rowdot;      // R [M, ld_rowdot] bf16
+    int64_t ld_rowdot;
+    float* rowdot_partial;     // [ksplit * tiles_n][M]
+    float* base_sq_partial;    // [ksplit][M] or nullptr
+};
+
+// number of N tiles the ROWDOT epilogue will produce partials for (depends on the tile chosen)
+int gemm_bf16_tiles_n(const GemmArgs& a);
+hipError_t launch_gemm_bf16(const GemmArgs& a, int trace_id, hipStream_t stream);
+
+// ---- fp32 GEMM (simple LDS-tiled VALU kernel; the fp32 configuration is small) ------------------
+struct SgemmSeg {
+    const float* a;
+    const float* b;
+    int64_t sa_m, sa_k, sb_n, sb_k;  // element strides
+    int K;
+};
+struct SgemmArgs {
+    SgemmSeg seg[2];
+    int nseg;
+    int M, N;
+    float alpha;
+    float* c;
+    int64_t ldc;
+};
+hipError_t launch_sgemm_f32(const SgemmArgs& a, int trace_id, hipStream_t stream);
+
+// ---- element-wise / reduction kernels -----------------------------------------------------------
+hipError_t launch_mag_scale(const float* m, const float* c, float eps, float* g, float* gm1, int d_out, hipStream_t st);
+hipError_t launch_compose_fwd(int dtype, const void* base, const void* lora, const float* g, const float* gm1, float s,
+                              void* out, int write_delta, void* inner, int64_t tokens, int d_out, hipStream_t st);
+int compose_bwd_slabs(int64_t tokens);
+hipError_t launch_compose_bwd(int dtype, const void* dy, const void* inner, const float* g, void* dz,
+                              float* partial /* [slabs][d_out] or nullptr */, int64_t tokens, int d_out, hipStream_t st);
+hipError_t launch_dm_final(const float* partial, int slabs, const float* c, float eps, float* dm, int d_out, hipStream_t st);
+hipError_t launch_gram_reduce(const float* partials, int ksplit, int r, float* G, bf16_t* Ghi, bf16_t* Glo, hipStream_t st);
+hipError_t launch_norm_final(const float* base_sq_p, int n_base, const float* cross_p, int n_cross, const float* ba_p,
+                             int n_ba, double s, float* c, int d_out, hipStream_t st);
+hipError_t launch_rownorm_s0_bf16(const bf16_t* W, float* c, int d_out, int d_in, hipStream_t st);
+// fp32 path: base_sq, cross, ba_sq and Eq. 5 from W, B, U = W A^T, BG = B G (all fp32)
+hipError_t launch_rownorm_f32(const float* W, const float* B, const float* U, const float* BG, double s, float* c,
+                              int d_out, int d_in, int r, hipStream_t st);
+
+}  // namespace dora

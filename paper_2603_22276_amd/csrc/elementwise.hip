@@ -1,0 +1,399 @@
+// Element-wise and reduction kernels of the DoRA hot path: magnitude scale (Eq. 6), norm assembly
+// (Eq. 5), compose forward (Sec. 3.1, App. C item 1), compose backward with the fused two-stage
+// column reduction for the magnitude gradient (Sec. 3.2; Sec. 7 "LLM-guided optimization").
+//
+// All of these are HBM streams: every thread moves 16-byte vectors, a workgroup owns a fixed set
+// of columns (so g / gm1 live in registers) and walks down a slab of token rows.
+#include "common.hpp"
+
+namespace dora {
+
+namespace {
+
+constexpr int CW = 64;  // threads along the column direction (one 16-byte vector each)
+constexpr int CH = 4;   // threads along the row direction
+
+template <typename T> struct Vec;
+template <> struct Vec<bf16_t> {
+    static constexpr int N = 8;
+    typedef uint4 raw_t;
+    static __device__ __forceinline__ void unpack(const raw_t& r, float* f)
+    {
+        f[0] = bf16_lo(r.x); f[1] = bf16_hi(r.x); f[2] = bf16_lo(r.y); f[3] = bf16_hi(r.y);
+        f[4] = bf16_lo(r.z); f[5] = bf16_hi(r.z); f[6] = bf16_lo(r.w); f[7] = bf16_hi(r.w);
+    }
+    static __device__ __forceinline__ raw_t pack(const float* f)
+    {
+        raw_t r;
+        r.x = pack_bf16x2(f[0], f[1]); r.y = pack_bf16x2(f[2], f[3]);
+        r.z = pack_bf16x2(f[4], f[5]); r.w = pack_bf16x2(f[6], f[7]);
+        return r;
+    }
+};
+template <> struct Vec<float> {
+    static constexpr int N = 4;
+    typedef float4 raw_t;
+    static __device__ __forceinline__ void unpack(const raw_t& r, float* f) { f[0] = r.x; f[1] = r.y; f[2] = r.z; f[3] = r.w; }
+    static __device__ __forceinline__ raw_t pack(const float* f) { return make_float4(f[0], f[1], f[2], f[3]); }
+};
+
+// ------------------------------------------------------------------------------------------------
+// Eq. 6 and the explicit small correction of Sec. 3.1.
+__global__ void mag_scale_kernel(const float* __restrict__ m, const float* __restrict__ c, float eps,
+                                 float* __restrict__ g, float* __restrict__ gm1, int d_out)
+{
+    int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= d_out) return;
+    float cj = c[j];
+    float cc = (cj < eps) ? eps : cj;  // NaN stays NaN
+    float mj = m[j];
+    if (g) g[j] = mj / cc;
+    if (gm1) gm1[j] = (mj - cc) / cc;  // the subtraction is exact when m/cc is within [1/2, 2]
+}
+
+// Eq. 5 from the partial sums the norm kernels left behind; partials are added in index order.
+__global__ void norm_final_kernel(const float* __restrict__ base_p, int n_base, const float* __restrict__ cross_p,
+                                  int n_cross, const float* __restrict__ ba_p, int n_ba, float two_s, float s2,
+                                  float* __restrict__ c, int d_out)
+{
+    int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= d_out) return;
+    float base_sq = 0.f, cross = 0.f, ba = 0.f;
+    for (int i = 0; i < n_base; ++i) base_sq += base_p[(int64_t)i * d_out + j];
+    for (int i = 0; i < n_cross; ++i) cross += cross_p[(int64_t)i * d_out + j];
+    for (int i = 0; i < n_ba; ++i) ba += ba_p[(int64_t)i * d_out + j];
+    float rad = base_sq + two_s * cross + s2 * ba;
+    rad = (rad < 0.f) ? 0.f : rad;  // NaN is not < 0: it propagates (App. C item 3)
+    c[j] = __fsqrt_rn(rad);
+}
+
+// G = sum of split-K partials (fixed order), and its two-term bf16 expansion G ~ Ghi + Glo.
+__global__ void gram_reduce_kernel(const float* __restrict__ p, int ksplit, int rr, float* __restrict__ G,
+                                   bf16_t* __restrict__ Ghi, bf16_t* __restrict__ Glo)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= rr) return;
+    float acc = 0.f;
+    for (int z = 0; z < ksplit; ++z) acc += p[(int64_t)z * rr + i];
+    if (G) G[i] = acc;
+    uint32_t hi = f32_to_bf16_bits(acc);
+    float rem = acc - __uint_as_float(hi << 16);
+    Ghi[i] = (bf16_t)hi;
+    Glo[i] = (bf16_t)f32_to_bf16_bits(rem);
+}
+
+// fp32 configuration: the three terms of Eq. 2 for one row per wavefront, from U = W A^T and BG = B G.
+__global__ void rownorm_f32_kernel(const float* __restrict__ W, const float* __restrict__ B, const float* __restrict__ U,
+                                   const float* __restrict__ BG, float two_s, float s2, float* __restrict__ c,
+                                   int d_out, int d_in, int r)
+{
+    int lane = threadIdx.x & 63;
+    int row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (row >= d_out) return;
+    float base_sq = 0.f, cross = 0.f, ba = 0.f;
+    const float* w = W + (int64_t)row * d_in;
+    for (int k = lane; k < d_in; k += 64) { float v = w[k]; base_sq = fmaf(v, v, base_sq); }
+    if (U) {
+        const float* b = B + (int64_t)row * r;
+        const float* u = U + (int64_t)row * r;
+        const float* bg = BG + (int64_t)row * r;
+        for (int l = lane; l < r; l += 64) { float bv = b[l]; cross = fmaf(bv, u[l], cross); ba = fmaf(bv, bg[l], ba); }
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        base_sq += __shfl_xor(base_sq, o);
+        cross += __shfl_xor(cross, o);
+        ba += __shfl_xor(ba, o);
+    }
+    if (lane == 0) {
+        float rad = base_sq + two_s * cross + s2 * ba;
+        rad = (rad < 0.f) ? 0.f : rad;
+        c[row] = __fsqrt_rn(rad);
+    }
+}
+
+// s == 0 (Algorithm 1, notes): the norm is the row norm of W alone.  One wavefront per row, bf16 storage.
+__global__ void rownorm_s0_bf16_kernel(const bf16_t* __restrict__ W, float* __restrict__ c, int d_out, int d_in)
+{
+    int lane = threadIdx.x & 63;
+    int row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (row >= d_out) return;
+    const bf16_t* w = W + (int64_t)row * d_in;
+    float acc = 0.f;
+    for (int k = lane * 8; k < d_in; k += 64 * 8) {
+        uint4 v = *reinterpret_cast<const uint4*>(w + k);
+        float f[8];
+        Vec<bf16_t>::unpack(v, f);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc = fmaf(f[i], f[i], acc);
+    }
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+    if (lane == 0) c[row] = __fsqrt_rn(acc);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Compose forward.  delta = gm1*base + g*(s*lora);  out = delta or base + delta;  inner = s*lora + base.
+// OUTMODE: 0 = no out tensor (inner only), 1 = out = base + delta, 2 = out = delta.
+template <typename T, int OUTMODE, bool INNER>
+__global__ __launch_bounds__(CW* CH) void compose_fwd_kernel(const T* base_, const T* lora_,  // out may alias base, inner may alias lora
+                                                             
+                                                              const float* __restrict__ g, const float* __restrict__ gm1,
+                                                              float s, T* out_, T* inner_, int64_t tokens, int d_out,
+                                                              int rows_per_wg)
+{
+    typedef Vec<T> V;
+    typedef typename V::raw_t raw_t;
+    constexpr int N = V::N;
+    const int col = (blockIdx.x * CW + threadIdx.x) * N;
+    if (col >= d_out) return;
+    float gv[N], g1[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        gv[i] = g[col + i];
+        g1[i] = gm1 ? gm1[col + i] : gv[i] - 1.0f;
+    }
+    const int64_t row_begin = (int64_t)blockIdx.y * rows_per_wg;
+    int64_t row_end = row_begin + rows_per_wg;
+    if (row_end > tokens) row_end = tokens;
+    constexpr int UNROLL = 4;
+    for (int64_t row = row_begin + threadIdx.y; row < row_end; row += CH * UNROLL) {
+        raw_t b[UNROLL], l[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            int64_t rr = row + u * CH;
+            if (rr < row_end) {
+                b[u] = *reinterpret_cast<const raw_t*>(base_ + rr * d_out + col);
+                l[u] = *reinterpret_cast<const raw_t*>(lora_ + rr * d_out + col);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            int64_t rr = row + u * CH;
+            if (rr < row_end) {
+                float bf[N], lf[N], of[N], inf[N];
+                V::unpack(b[u], bf);
+                V::unpack(l[u], lf);
+#pragma unroll
+                for (int i = 0; i < N; ++i) {
+                    float sl = s * lf[i];                        // canonical order: s*lora first, then g*(.)
+                    float delta = fmaf(g1[i], bf[i], gv[i] * sl);
+                    of[i] = (OUTMODE == 2) ? delta : bf[i] + delta;
+                    inf[i] = sl + bf[i];
+                }
+                if (OUTMODE != 0) *reinterpret_cast<raw_t*>(out_ + rr * d_out + col) = V::pack(of);
+                if (INNER) *reinterpret_cast<raw_t*>(inner_ + rr * d_out + col) = V::pack(inf);
+            }
+        }
+    }
+}
+
+// Compose backward: dz = g*dy, and (DM) the first stage of the column sum of dy*inner over this slab.
+template <typename T, bool DM>
+__global__ __launch_bounds__(CW* CH) void compose_bwd_kernel(const T* __restrict__ dy_, const T* __restrict__ inner_,
+                                                              const float* __restrict__ g, T* __restrict__ dz_,
+                                                              float* __restrict__ partial, int64_t tokens, int d_out,
+                                                              int rows_per_wg)
+{
+    typedef Vec<T> V;
+    typedef typename V::raw_t raw_t;
+    constexpr int N = V::N;
+    __shared__ float red[CH][CW * N];
+    const int col = (blockIdx.x * CW + threadIdx.x) * N;
+    const bool active = col < d_out;
+    float gv[N], acc[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        gv[i] = active ? g[col + i] : 0.f;
+        acc[i] = 0.f;
+    }
+    const int64_t row_begin = (int64_t)blockIdx.y * rows_per_wg;
+    int64_t row_end = row_begin + rows_per_wg;
+    if (row_end > tokens) row_end = tokens;
+    constexpr int UNROLL = 4;
+    if (active) {
+        for (int64_t row = row_begin + threadIdx.y; row < row_end; row += CH * UNROLL) {
+            raw_t d[UNROLL], in[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                int64_t rr = row + u * CH;
+                if (rr < row_end) {
+                    d[u] = *reinterpret_cast<const raw_t*>(dy_ + rr * d_out + col);
+                    if (DM) in[u] = *reinterpret_cast<const raw_t*>(inner_ + rr * d_out + col);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                int64_t rr = row + u * CH;
+                if (rr < row_end) {
+                    float df[N], nf[N], zf[N];
+                    V::unpack(d[u], df);
+                    if (DM) V::unpack(in[u], nf);
+#pragma unroll
+                    for (int i = 0; i < N; ++i) {
+                        zf[i] = gv[i] * df[i];
+                        if (DM) acc[i] = fmaf(df[i], nf[i], acc[i]);
+                    }
+                    *reinterpret_cast<raw_t*>(dz_ + rr * d_out + col) = V::pack(zf);
+                }
+            }
+        }
+    }
+    if (DM) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) red[threadIdx.y][threadIdx.x * N + i] = acc[i];
+        __syncthreads();
+        if (threadIdx.y == 0 && active) {
+#pragma unroll
+            for (int i = 0; i < N; ++i) {
+                float v = red[0][threadIdx.x * N + i];
+                for (int y = 1; y < CH; ++y) v += red[y][threadIdx.x * N + i];  // fixed order
+                partial[(int64_t)blockIdx.y * d_out + col + i] = v;
+            }
+        }
+    }
+}
+
+// Second stage: dm[j] = (sum over slabs, in slab order) / max(c[j], eps).
+constexpr int DMF_W = 64, DMF_H = 4;
+__global__ __launch_bounds__(DMF_W* DMF_H) void dm_final_kernel(const float* __restrict__ partial, int slabs,
+                                                                 const float* __restrict__ c, float eps,
+                                                                 float* __restrict__ dm, int d_out)
+{
+    __shared__ float red[DMF_H][DMF_W];
+    int j = blockIdx.x * DMF_W + threadIdx.x;
+    float acc = 0.f;
+    if (j < d_out) {
+        // each of the DMF_H thread rows owns a contiguous range of slabs
+        int per = (slabs + DMF_H - 1) / DMF_H;
+        int z0 = threadIdx.y * per;
+        int z1 = z0 + per < slabs ? z0 + per : slabs;
+        for (int z = z0; z < z1; ++z) acc += partial[(int64_t)z * d_out + j];
+    }
+    red[threadIdx.y][threadIdx.x] = acc;
+    __syncthreads();
+    if (threadIdx.y == 0 && j < d_out) {
+        float v = red[0][threadIdx.x];
+        for (int y = 1; y < DMF_H; ++y) v += red[y][threadIdx.x];
+        float cj = c[j];
+        float cc = (cj < eps) ? eps : cj;
+        dm[j] = v / cc;
+    }
+}
+
+constexpr int FWD_ROWS_PER_WG = 64;
+constexpr int BWD_ROWS_PER_WG = 64;
+
+}  // namespace
+
+hipError_t launch_mag_scale(const float* m, const float* c, float eps, float* g, float* gm1, int d_out, hipStream_t st)
+{
+    if (d_out == 0) return hipSuccess;
+    TraceScope ts(DORA_K_MAG_SCALE, st);
+    mag_scale_kernel<<<dim3((d_out + 255) / 256), dim3(256), 0, st>>>(m, c, eps, g, gm1, d_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_norm_final(const float* base_p, int n_base, const float* cross_p, int n_cross, const float* ba_p,
+                             int n_ba, double s, float* c, int d_out, hipStream_t st)
+{
+    if (d_out == 0) return hipSuccess;
+    TraceScope ts(DORA_K_NORM_FINAL, st);
+    // 2s and s^2 are formed in double and rounded once (App. C item 3)
+    norm_final_kernel<<<dim3((d_out + 255) / 256), dim3(256), 0, st>>>(base_p, n_base, cross_p, n_cross, ba_p, n_ba,
+                                                                       (float)(2.0 * s), (float)(s * s), c, d_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_gram_reduce(const float* partials, int ksplit, int r, float* G, bf16_t* Ghi, bf16_t* Glo, hipStream_t st)
+{
+    int rr = r * r;
+    if (rr == 0) return hipSuccess;
+    TraceScope ts(DORA_K_GRAM_REDUCE, st);
+    gram_reduce_kernel<<<dim3((rr + 255) / 256), dim3(256), 0, st>>>(partials, ksplit, rr, G, Ghi, Glo);
+    return hipGetLastError();
+}
+
+hipError_t launch_rownorm_s0_bf16(const bf16_t* W, float* c, int d_out, int d_in, hipStream_t st)
+{
+    if (d_out == 0) return hipSuccess;
+    TraceScope ts(DORA_K_NORM_FINAL, st);
+    rownorm_s0_bf16_kernel<<<dim3((d_out + 3) / 4), dim3(256), 0, st>>>(W, c, d_out, d_in);
+    return hipGetLastError();
+}
+
+hipError_t launch_rownorm_f32(const float* W, const float* B, const float* U, const float* BG, double s, float* c,
+                              int d_out, int d_in, int r, hipStream_t st)
+{
+    if (d_out == 0) return hipSuccess;
+    TraceScope ts(DORA_K_NORM_FINAL, st);
+    rownorm_f32_kernel<<<dim3((d_out + 3) / 4), dim3(256), 0, st>>>(W, B, U, BG, (float)(2.0 * s), (float)(s * s), c,
+                                                                    d_out, d_in, r);
+    return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t compose_fwd_t(const void* base, const void* lora, const float* g, const float* gm1, float s, void* out,
+                                int write_delta, void* inner, int64_t tokens, int d_out, hipStream_t st)
+{
+    constexpr int N = Vec<T>::N;
+    int cpr = d_out / N;
+    dim3 grid((cpr + CW - 1) / CW, (unsigned)((tokens + FWD_ROWS_PER_WG - 1) / FWD_ROWS_PER_WG));
+    dim3 block(CW, CH);
+    const T* b = (const T*)base;
+    const T* l = (const T*)lora;
+    T* o = (T*)out;
+    T* in = (T*)inner;
+#define DORA_LAUNCH_FWD(D, I) \
+    compose_fwd_kernel<T, D, I><<<grid, block, 0, st>>>(b, l, g, gm1, s, o, in, tokens, d_out, FWD_ROWS_PER_WG)
+    if (!out) { DORA_LAUNCH_FWD(0, true); }
+    else if (write_delta) { if (inner) DORA_LAUNCH_FWD(2, true); else DORA_LAUNCH_FWD(2, false); }
+    else { if (inner) DORA_LAUNCH_FWD(1, true); else DORA_LAUNCH_FWD(1, false); }
+#undef DORA_LAUNCH_FWD
+    return hipGetLastError();
+}
+
+hipError_t launch_compose_fwd(int dtype, const void* base, const void* lora, const float* g, const float* gm1, float s,
+                              void* out, int write_delta, void* inner, int64_t tokens, int d_out, hipStream_t st)
+{
+    if (tokens == 0 || d_out == 0) return hipSuccess;
+    TraceScope ts(DORA_K_COMPOSE_FWD, st);
+    if (dtype == DORA_BF16) return compose_fwd_t<bf16_t>(base, lora, g, gm1, s, out, write_delta, inner, tokens, d_out, st);
+    return compose_fwd_t<float>(base, lora, g, gm1, s, out, write_delta, inner, tokens, d_out, st);
+}
+
+int compose_bwd_slabs(int64_t tokens) { return (int)((tokens + BWD_ROWS_PER_WG - 1) / BWD_ROWS_PER_WG); }
+
+template <typename T>
+static hipError_t compose_bwd_t(const void* dy, const void* inner, const float* g, void* dz, float* partial,
+                                int64_t tokens, int d_out, hipStream_t st)
+{
+    constexpr int N = Vec<T>::N;
+    int cpr = d_out / N;
+    dim3 grid((cpr + CW - 1) / CW, (unsigned)compose_bwd_slabs(tokens));
+    dim3 block(CW, CH);
+    if (partial)
+        compose_bwd_kernel<T, true><<<grid, block, 0, st>>>((const T*)dy, (const T*)inner, g, (T*)dz, partial, tokens,
+                                                             d_out, BWD_ROWS_PER_WG);
+    else
+        compose_bwd_kernel<T, false><<<grid, block, 0, st>>>((const T*)dy, nullptr, g, (T*)dz, nullptr, tokens, d_out,
+                                                              BWD_ROWS_PER_WG);
+    return hipGetLastError();
+}
+
+hipError_t launch_compose_bwd(int dtype, const void* dy, const void* inner, const float* g, void* dz, float* partial,
+                              int64_t tokens, int d_out, hipStream_t st)
+{
+    if (tokens == 0 || d_out == 0) return hipSuccess;
+    TraceScope ts(DORA_K_COMPOSE_BWD, st);
+    if (dtype == DORA_BF16) return compose_bwd_t<bf16_t>(dy, inner, g, dz, partial, tokens, d_out, st);
+    return compose_bwd_t<float>(dy, inner, g, dz, partial, tokens, d_out, st);
+}
+
+hipError_t launch_dm_final(const float* partial, int slabs, const float* c, float eps, float* dm, int d_out, hipStream_t st)
+{
+    if (d_out == 0) return hipSuccess;
+    TraceScope ts(DORA_K_DM_FINAL, st);
+    dm_final_kernel<<<dim3((d_out + DMF_W - 1) / DMF_W), dim3(DMF_W, DMF_H), 0, st>>>(partial, slabs, c, eps, dm, d_out);
+    return hipGetLastError();
+}
+
+}  // namespace dora

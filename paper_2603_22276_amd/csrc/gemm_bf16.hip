@@ -1,0 +1,351 @@
+// bf16 MFMA GEMM family for gfx950 (CDNA4), fp32 accumulation.
+//
+//   C[M,N] = alpha * sum_seg sum_k Aop[m,k] * Bop[n,k]
+//
+// One kernel template serves every dense contraction of the DoRA module: x W^T, x A^T, h B^T
+// (both operands K-contiguous), dz W + dh A and dz B (N-side operand K-strided), dh^T x and dz^T h
+// (both K-strided), and the factored-norm products of Sec. 2: U = W A^T with the row-dot epilogue
+// of Eq. 3 (U never leaves registers), G = A A^T (Eq. 4, split-K partials), and rowdot(B, B G).
+//
+// Structure (per workgroup): a BM x BN tile of C, K walked in steps of 64.  Global -> registers ->
+// LDS double buffer (XOR-swizzled 16-byte chunks so MFMA operand reads spread over the banks),
+// v_mfma_f32_32x32x16_bf16 on 64-wide wavefronts, each wave owning a (BM/WGM) x (BN/WGN) sub-tile.
+// The N-side fragment is fed as the MFMA's first operand so that every lane ends up holding four
+// consecutive n for one m, which makes the epilogue's stores and row-dots vector-friendly.
+// Workgroup ids are remapped so that each of the 8 XCDs (own L2 each) works on a compact block of
+// tiles, walked in groups of 8 tile-rows.
+#include "common.hpp"
+
+namespace dora {
+namespace {
+
+constexpr int BK = 64;          // K step per LDS stage (elements)
+constexpr int CPR = BK / 8;     // 16-byte chunks per LDS row
+constexpr int NUM_XCD = 8;
+constexpr int GROUP_M = 8;
+
+template <int BM_, int BN_, int WGM_, int WGN_>
+struct Tile {
+    static constexpr int BM = BM_, BN = BN_, WGM = WGM_, WGN = WGN_;
+    static constexpr int WAVES = WGM * WGN, THREADS = 64 * WAVES;
+    static constexpr int WM = BM / WGM, WN = BN / WGN;
+    static constexpr int MT = WM / 32, NT = WN / 32;
+    static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int NLA = BM * CPR / THREADS;  // 16-byte global loads per thread per stage, M side
+    static constexpr int NLB = BN * CPR / THREADS;
+    static constexpr int EPI_BYTES_PER_WAVE = 32 * (WN * 4 + 16);
+    static constexpr int LDS_BYTES =
+        (2 * STAGE_BYTES > WAVES * EPI_BYTES_PER_WAVE) ? 2 * STAGE_BYTES : WAVES * EPI_BYTES_PER_WAVE;
+    static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
+    static_assert((BM * CPR) % THREADS == 0 && (BN * CPR) % THREADS == 0, "load plan must divide evenly");
+};
+
+typedef Tile<256, 256, 2, 4> TileBig;   // 512 threads, 128 KB of LDS, 128 accumulator registers per lane
+typedef Tile<128, 128, 2, 2> TileMed;   // 256 threads,  64 KB of LDS, two workgroups fit a CU
+
+// byte offset of element (row, k) in a swizzled [rows][BK] bf16 LDS tile
+__device__ __forceinline__ int lds_off(int row, int k)
+{
+    return row * (BK * 2) + ((((k >> 3) ^ row) & (CPR - 1)) << 4) + ((k & 7) << 1);
+}
+
+template <int ROWS, int NL, int THREADS, bool KCONTIG>
+struct OperandLoader {
+    // Loads one [ROWS x BK] operand tile into registers; invalid chunks read as zero.
+    static __device__ __forceinline__ void gload(uint4 (&reg)[NL], const bf16_t* __restrict__ base, int64_t ld,
+                                                 int row0, int rows, int k0, int K, int tid)
+    {
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            int c = tid + i * THREADS;
+            int row, k;
+            if (KCONTIG) { row = c / CPR; k = (c % CPR) * 8; }
+            else { k = c / (ROWS / 8); row = (c % (ROWS / 8)) * 8; }
+            int grow = row0 + row, gk = k0 + k;
+            bool ok = (grow < rows) && (gk < K);
+            const bf16_t* p = KCONTIG ? base + (int64_t)grow * ld + gk : base + (int64_t)gk * ld + grow;
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (ok) v = *reinterpret_cast<const uint4*>(p);
+            reg[i] = v;
+        }
+    }
+    static __device__ __forceinline__ void lstore(const uint4 (&reg)[NL], char* tile, int tid)
+    {
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            int c = tid + i * THREADS;
+            if (KCONTIG) {
+                int row = c / CPR, k = (c % CPR) * 8;
+                *reinterpret_cast<uint4*>(tile + lds_off(row, k)) = reg[i];
+            } else {
+                // the chunk holds 8 consecutive rows at one k: scatter them (transposing store)
+                int k = c / (ROWS / 8), row = (c % (ROWS / 8)) * 8;
+                uint32_t w[4] = {reg[i].x, reg[i].y, reg[i].z, reg[i].w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    uint16_t v = (uint16_t)((e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xffffu));
+                    *reinterpret_cast<uint16_t*>(tile + lds_off(row + e, k)) = v;
+                }
+            }
+        }
+    }
+};
+
+struct TileCoord { int tm, tn, z; };
+
+// Workgroup id -> (tile row, tile column, K slice).  Hardware hands consecutive ids to the XCDs
+// round-robin; undo that so each XCD owns a contiguous range of logical ids, then walk tiles in
+// groups of GROUP_M rows so that co-resident tiles share operand panels in that XCD's L2.
+__device__ __forceinline__ TileCoord map_tile(int wg, int tiles_m, int tiles_n, int ksplit)
+{
+    int total = tiles_m * tiles_n * ksplit;
+    int q = total / NUM_XCD, rem = total % NUM_XCD;
+    int xcd = wg % NUM_XCD, idx = wg / NUM_XCD;
+    int logical = (xcd < rem) ? xcd * (q + 1) + idx : rem * (q + 1) + (xcd - rem) * q + idx;
+    int tiles = tiles_m * tiles_n;
+    TileCoord t;
+    t.z = logical / tiles;
+    int id = logical % tiles;
+    int per_group = GROUP_M * tiles_n;
+    int group = id / per_group;
+    int first_m = group * GROUP_M;
+    int gsz = tiles_m - first_m < GROUP_M ? tiles_m - first_m : GROUP_M;
+    int in_group = id % per_group;
+    t.tm = first_m + in_group % gsz;
+    t.tn = in_group / gsz;
+    return t;
+}
+
+template <class T, bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmArgs p)
+{
+    constexpr int BM = T::BM, BN = T::BN, MT = T::MT, NT = T::NT, THREADS = T::THREADS;
+    __shared__ __attribute__((aligned(16))) char smem[T::LDS_BYTES];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int wm = wave / T::WGN, wn = wave % T::WGN;
+    const int wm0 = wm * T::WM, wn0 = wn * T::WN;
+
+    const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+    const TileCoord tc = map_tile(blockIdx.x, tiles_m, tiles_n, p.ksplit);
+    const int m0 = tc.tm * BM, n0 = tc.tn * BN;
+
+    // flattened K-tile schedule over the segments; split-K slices segment 0 only
+    const int kt0_total = (p.seg[0].K + BK - 1) / BK;
+    const int kt1_total = (p.nseg > 1) ? (p.seg[1].K + BK - 1) / BK : 0;
+    int t_begin = 0, t_end = kt0_total + kt1_total;
+    if (p.ksplit > 1) {
+        int per = (kt0_total + p.ksplit - 1) / p.ksplit;
+        t_begin = tc.z * per;
+        t_end = t_begin + per < kt0_total ? t_begin + per : kt0_total;
+        if (t_end < t_begin) t_end = t_begin;
+    }
+
+    f32x16_t acc[MT][NT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    float bsq[MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) bsq[i] = 0.f;
+    const bool want_bsq = (EPI == EPI_ROWDOT) && (p.base_sq_partial != nullptr) && (tc.tn == 0);
+
+    typedef OperandLoader<BM, T::NLA, THREADS, A_KC> LA;
+    typedef OperandLoader<BN, T::NLB, THREADS, B_KC> LB;
+    uint4 ra[T::NLA], rb[T::NLB];
+
+    auto gload = [&](int t) {
+        const int s = (t >= kt0_total) ? 1 : 0;
+        const int k0 = (s ? t - kt0_total : t) * BK;
+        const GemmSeg& sg = p.seg[s];
+        LA::gload(ra, sg.a, sg.lda, m0, p.M, k0, sg.K, tid);
+        LB::gload(rb, sg.b, sg.ldb, n0, p.N, k0, sg.K, tid);
+    };
+    auto lstore = [&](int stage) {
+        char* st = smem + stage * T::STAGE_BYTES;
+        LA::lstore(ra, st, tid);
+        LB::lstore(rb, st + T::A_BYTES, tid);
+    };
+
+    if (t_begin < t_end) {
+        gload(t_begin);
+        lstore(0);
+    }
+    __syncthreads();
+
+    for (int t = t_begin; t < t_end; ++t) {
+        const int stage = (t - t_begin) & 1;
+        if (t + 1 < t_end) gload(t + 1);
+        const char* sa = smem + stage * T::STAGE_BYTES;
+        const char* sb = sa + T::A_BYTES;
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            bf16x8_t af[MT], bfr[NT];
+            const int k = kk * 16 + lh * 8;
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+                af[i] = *reinterpret_cast<const bf16x8_t*>(sa + lds_off(wm0 + i * 32 + l32, k));
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+                bfr[j] = *reinterpret_cast<const bf16x8_t*>(sb + lds_off(wn0 + j * 32 + l32, k));
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+            if (EPI == EPI_ROWDOT) {
+                // base term of Eq. 2: sum of squares of the M-side rows, taken from the fragments
+                // already in registers; the waves along N share the K steps between them
+                if (want_bsq && (kk % T::WGN) == wn) {
+#pragma unroll
+                    for (int i = 0; i < MT; ++i) {
+                        uint4 u = __builtin_bit_cast(uint4, af[i]);
+                        uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            float lo = bf16_lo(w[e]), hi = bf16_hi(w[e]);
+                            bsq[i] = fmaf(lo, lo, bsq[i]);
+                            bsq[i] = fmaf(hi, hi, bsq[i]);
+                        }
+                    }
+                }
+            }
+        }
+        if (t + 1 < t_end) lstore(stage ^ 1);
+        __syncthreads();
+    }
+
+    // ------------------------------------------------------------------------------ epilogues
+    if (EPI == EPI_ROWDOT) {
+        float* red = reinterpret_cast<float*>(smem);          // [WGN][BM] row-dot, then [WGN][BM] base_sq
+        float* red2 = red + T::WGN * BM;
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+            const int mg = m0 + wm0 + i * 32 + l32;
+            float rs = 0.f;
+            if (mg < p.M) {
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const int ng = n0 + wn0 + j * 32 + b * 8 + lh * 4;
+                        if (ng < p.N) {
+                            uint2 rv = *reinterpret_cast<const uint2*>(p.rowdot + (int64_t)mg * p.ld_rowdot + ng);
+                            rs = fmaf(acc[i][j][b * 4 + 0], bf16_lo(rv.x), rs);
+                            rs = fmaf(acc[i][j][b * 4 + 1], bf16_hi(rv.x), rs);
+                            rs = fmaf(acc[i][j][b * 4 + 2], bf16_lo(rv.y), rs);
+                            rs = fmaf(acc[i][j][b * 4 + 3], bf16_hi(rv.y), rs);
+                        }
+                    }
+            }
+            rs += __shfl_xor(rs, 32);
+            float bq = bsq[i] + __shfl_xor(bsq[i], 32);
+            if (lh == 0) {
+                red[wn * BM + wm0 + i * 32 + l32] = rs;
+                red2[wn * BM + wm0 + i * 32 + l32] = bq;
+            }
+        }
+        __syncthreads();
+        if (tid < BM && m0 + tid < p.M) {
+            float v = red[tid], q = red2[tid];
+            for (int w = 1; w < T::WGN; ++w) { v += red[w * BM + tid]; q += red2[w * BM + tid]; }
+            p.rowdot_partial[(int64_t)(tc.z * tiles_n + tc.tn) * p.M + m0 + tid] = v;
+            if (want_bsq) p.base_sq_partial[(int64_t)tc.z * p.M + m0 + tid] = q;
+        }
+        return;
+    }
+
+    // STORE: stage each 32-row band of the wave's sub-tile through LDS, then write whole 16-byte
+    // vectors along N.
+    constexpr bool OUT_BF16 = (EPI == EPI_STORE_BF16);
+    constexpr int ESZ = OUT_BF16 ? 2 : 4;
+    constexpr int ROW_BYTES = T::WN * ESZ + 16;
+    constexpr int CHUNKS_PER_ROW = T::WN * ESZ / 16;
+    constexpr int ROWS_PER_PASS = 64 / CHUNKS_PER_ROW;
+    char* stg = smem + wave * T::EPI_BYTES_PER_WAVE;
+    char* cbase = reinterpret_cast<char*>(p.c) + (p.ksplit > 1 ? (int64_t)tc.z * p.M * p.ldc * ESZ : 0);
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int col = j * 32 + b * 8 + lh * 4;
+                float v0 = p.alpha * acc[i][j][b * 4 + 0], v1 = p.alpha * acc[i][j][b * 4 + 1];
+                float v2 = p.alpha * acc[i][j][b * 4 + 2], v3 = p.alpha * acc[i][j][b * 4 + 3];
+                if (OUT_BF16) {
+                    uint2 o;
+                    o.x = pack_bf16x2(v0, v1);
+                    o.y = pack_bf16x2(v2, v3);
+                    *reinterpret_cast<uint2*>(stg + l32 * ROW_BYTES + col * 2) = o;
+                } else {
+                    *reinterpret_cast<float4*>(stg + l32 * ROW_BYTES + col * 4) = make_float4(v0, v1, v2, v3);
+                }
+            }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int ps = 0; ps < 32 / ROWS_PER_PASS; ++ps) {
+            const int row = ps * ROWS_PER_PASS + lane / CHUNKS_PER_ROW;
+            const int ch = lane % CHUNKS_PER_ROW;
+            uint4 v = *reinterpret_cast<const uint4*>(stg + row * ROW_BYTES + ch * 16);
+            const int mg = m0 + wm0 + i * 32 + row;
+            const int ng = n0 + wn0 + ch * (16 / ESZ);
+            if (mg < p.M && ng < p.N)
+                *reinterpret_cast<uint4*>(cbase + ((int64_t)mg * p.ldc + ng) * ESZ) = v;
+        }
+    }
+}
+
+template <class T>
+bool fits(const GemmArgs&) { return true; }
+
+template <class T, bool A_KC, bool B_KC, int EPI>
+hipError_t launch_one(const GemmArgs& a, hipStream_t stream)
+{
+    int tiles_m = (a.M + T::BM - 1) / T::BM, tiles_n = (a.N + T::BN - 1) / T::BN;
+    int grid = tiles_m * tiles_n * a.ksplit;
+    if (grid == 0) return hipSuccess;
+    gemm_bf16_kernel<T, A_KC, B_KC, EPI><<<dim3(grid), dim3(T::THREADS), 0, stream>>>(a);
+    return hipGetLastError();
+}
+
+bool use_big(const GemmArgs& a)
+{
+    // the large tile pays off once it still yields a few tiles per CU
+    int64_t big_tiles = (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256);
+    return a.epilogue == EPI_STORE_BF16 && a.ksplit == 1 && big_tiles >= 256;
+}
+
+}  // namespace
+
+int gemm_bf16_tiles_n(const GemmArgs& a) { return (a.N + TileMed::BN - 1) / TileMed::BN; }
+
+hipError_t launch_gemm_bf16(const GemmArgs& a, int trace_id, hipStream_t stream)
+{
+    if (a.M == 0 || a.N == 0) return hipSuccess;
+    TraceScope ts(trace_id, stream);
+    const bool big = use_big(a);
+#define DORA_GEMM_CASE(AKC, BKC, E)                                                     \
+    if (a.a_kcontig == (AKC) && a.b_kcontig == (BKC) && a.epilogue == (E))              \
+        return big ? launch_one<TileBig, AKC, BKC, E>(a, stream) : launch_one<TileMed, AKC, BKC, E>(a, stream);
+    DORA_GEMM_CASE(true, true, EPI_STORE_BF16)
+    DORA_GEMM_CASE(true, false, EPI_STORE_BF16)
+#undef DORA_GEMM_CASE
+#define DORA_GEMM_CASE_MED(AKC, BKC, E)                                                 \
+    if (a.a_kcontig == (AKC) && a.b_kcontig == (BKC) && a.epilogue == (E))              \
+        return launch_one<TileMed, AKC, BKC, E>(a, stream);
+    DORA_GEMM_CASE_MED(true, true, EPI_STORE_F32)
+    DORA_GEMM_CASE_MED(true, true, EPI_ROWDOT)
+    DORA_GEMM_CASE_MED(false, false, EPI_STORE_F32)
+#undef DORA_GEMM_CASE_MED
+    return hipErrorInvalidValue;
+}
+
+}  // namespace dora

@@ -1,0 +1,287 @@
+"""GPU parity: every entry point of the C ABI against the fp64 CPU oracle, element by element,
+on the same seeded inputs.  Sizes are chosen so the oracle finishes in seconds while the kernels still
+cross several tiles and end in ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dora_oracle as O
+from paper_2603_22276_amd import binding as D
+from paper_2603_22276_amd import inputs as I
+
+import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+
+def cfg_bf16(name, d_out, d_in, r, tokens, sigma_B=1e-3, seed=0):
+    return I.DoraConfig(name, d_out, d_in, r, tokens, "bf16", 32.0, sigma_B, seed_offset=7000 + seed)
+
+
+def cfg_f32(name, d_out, d_in, r, tokens, sigma_B=1e-2, seed=0):
+    return I.DoraConfig(name, d_out, d_in, r, tokens, "f32", 16.0, sigma_B, seed_offset=8000 + seed)
+
+
+SMALL = [
+    I.C1,
+    cfg_f32("f32_ragged", 100, 52, 12, 33, seed=1),
+    cfg_bf16("bf16_ragged_tiny", 200, 328, 24, 77, seed=2),
+    cfg_bf16("bf16_ragged", 520, 392, 40, 300, seed=3),
+    I.stress(cfg_bf16("bf16_mid", 1024, 1536, 384, 640, seed=4)),
+    cfg_bf16("bf16_mid", 1024, 1536, 384, 640, seed=4),
+    cfg_bf16("bf16_bigtile_ragged", 4104, 264, 16, 4104, sigma_B=2e-2, seed=5),
+]
+IDS = [c.name for c in SMALL]
+
+
+def oracle_inputs(mod):
+    return dict(x=mod.f64("x"), W=mod.f64("W"), A=mod.f64("A"), B=mod.f64("B"),
+                m=mod.inp["m"].astype(np.float64), s=float(mod.inp["s"]), eps=mod.cfg.eps)
+
+
+# ----------------------------------------------------------------------------- norm (a1-a6)
+
+@pytest.mark.parametrize("cfg", SMALL, ids=IDS)
+def test_norm_matches_dense_oracle(cfg):
+    mod = G.Module(cfg)
+    c = G.to_f64(mod.norm())
+    ref = O.dense_row_norm(mod.f64("W"), mod.f64("A"), mod.f64("B"), float(mod.inp["s"]))
+    G.assert_norm_close(c, ref, G.TOL[cfg.dtype]["norm"])
+
+
+def test_norm_low_rank_terms_matter_in_stress_variant():
+    # guards the guard: in the stress variant dropping BA would be far outside tolerance
+    cfg = I.stress(cfg_bf16("bf16_mid", 1024, 1536, 384, 640, seed=4))
+    mod = G.Module(cfg)
+    ref = O.dense_row_norm(mod.f64("W"), mod.f64("A"), mod.f64("B"), float(mod.inp["s"]))
+    only_w = np.linalg.norm(mod.f64("W"), axis=1)
+    assert np.max(np.abs(only_w - ref) / ref) > 0.1
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_norm_special_cases(dtype):
+    mk = cfg_bf16 if dtype == "bf16" else cfg_f32
+    cfg = mk("special", 264, 200, 16, 8, seed=6)
+    inp = I.make_inputs(cfg)
+    tol = G.TOL[dtype]["norm"]
+    # B = 0: the row norm of W
+    inp0 = dict(inp); inp0["B"] = np.zeros_like(inp["B"])
+    mod = G.Module(cfg, inp0)
+    G.assert_norm_close(G.to_f64(mod.norm()), np.linalg.norm(mod.f64("W"), axis=1), tol)
+    # s = 0 fast path
+    mod = G.Module(cfg, inp)
+    mod.desc.s = 0.0
+    G.assert_norm_close(G.to_f64(mod.norm()), np.linalg.norm(mod.f64("W"), axis=1), tol)
+    # a zero row of W and of B gives norm 0 exactly, and g = m / eps stays finite
+    inpz = dict(inp); inpz["W"] = inp["W"].copy(); inpz["B"] = inp["B"].copy()
+    inpz["W"][3] = 0; inpz["B"][3] = 0
+    mod = G.Module(cfg, inpz)
+    c = mod.norm()
+    assert float(c[3]) == 0.0
+    g = G.empty_f32(cfg.d_out)
+    D.dora_mag_scale(mod.desc, mod.m, c, g, None)
+    ref_g = O.mag_scale(mod.inp["m"].astype(np.float64), G.to_f64(c), cfg.eps)
+    assert np.isfinite(float(g[3])) and abs(float(g[3]) - ref_g[3]) <= 1e-6 * abs(ref_g[3])
+
+
+def test_norm_nan_propagates():
+    cfg = cfg_bf16("nan", 136, 128, 16, 8, seed=7)
+    inp = I.make_inputs(cfg)
+    inp["W"] = inp["W"].copy(); inp["W"][5, 7] = 0x7FC0  # a NaN weight
+    c = G.to_f64(G.Module(cfg, inp).norm())
+    assert np.isnan(c[5]) and np.all(np.isfinite(np.delete(c, 5)))
+
+
+# ----------------------------------------------------------------------------- g (a6)
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_mag_scale(dtype):
+    rng = np.random.default_rng(1)
+    n = 1000
+    c = np.abs(rng.standard_normal(n)).astype(np.float32) + 0.5
+    c[:3] = [0.0, 1e-9, 1e-20]
+    m = (c.astype(np.float64) * (1 + 1e-3 * rng.standard_normal(n))).astype(np.float32)
+    m[:3] = 1.0
+    eps = 1e-6 if dtype == "bf16" else 1e-12
+    desc = D.make_desc(n, 8, 8, 0, G.dtype_code(dtype), 1.0)
+    g, gm1 = G.empty_f32(n), G.empty_f32(n)
+    D.dora_mag_scale(desc, G.to_dev(m), G.to_dev(c), g, gm1)
+    ref = O.mag_scale(m.astype(np.float64), c.astype(np.float64), eps)
+    np.testing.assert_allclose(G.to_f64(g), ref, rtol=2e-7)
+    # the explicit correction keeps full relative accuracy although g - 1 ~ 1e-3
+    np.testing.assert_allclose(G.to_f64(gm1)[3:], (ref - 1)[3:], rtol=1e-6, atol=1e-10)
+
+
+# ----------------------------------------------------------------------------- compose forward (a9)
+
+@pytest.mark.parametrize("dtype,tokens,d_out", [("f32", 64, 256), ("f32", 33, 100), ("bf16", 77, 200),
+                                               ("bf16", 300, 2056), ("bf16", 1, 8), ("bf16", 1030, 4096)])
+def test_compose_forward(dtype, tokens, d_out):
+    rng = np.random.default_rng(tokens * 7 + d_out)
+    base_s = I.quantise(rng.standard_normal((tokens, d_out)), dtype)
+    lora_s = I.quantise(rng.standard_normal((tokens, d_out)) * 0.02, dtype)
+    g64 = 1 + 0.0015 * rng.standard_normal(d_out)
+    g32 = g64.astype(np.float32)
+    gm1_32 = (g64 - 1).astype(np.float32)
+    s = np.float32(1.6329931)
+    desc = D.make_desc(d_out, 8, 8, tokens, G.dtype_code(dtype), float(s))
+    base, lora = G.to_dev(base_s), G.to_dev(lora_s)
+    ref_delta = O.compose_delta(I.to_f64(base_s), I.to_f64(lora_s), g32.astype(np.float64), float(s))
+    ref_inner = float(s) * I.to_f64(lora_s) + I.to_f64(base_s)
+    tol = G.TOL[dtype]["tensor"]
+    # delta with explicit gm1 (reference uses the same fp32 g, and gm1 as given)
+    ref_delta_gm1 = gm1_32.astype(np.float64)[None] * I.to_f64(base_s) + g32.astype(np.float64)[None] * (float(s) * I.to_f64(lora_s))
+    out, inner = G.empty((tokens, d_out), dtype), G.empty((tokens, d_out), dtype)
+    D.dora_compose(desc, base, lora, G.to_dev(g32), G.to_dev(gm1_32), out, 1, inner)
+    G.assert_close("delta(gm1)", G.to_f64(out), ref_delta_gm1, tol)
+    G.assert_close("inner", G.to_f64(inner), ref_inner, tol)
+    # delta with gm1 = NULL (g - 1 formed in fp32), and the y form
+    D.dora_compose(desc, base, lora, G.to_dev(g32), None, out, 1, None)
+    G.assert_close("delta", G.to_f64(out), ref_delta, tol)
+    D.dora_compose(desc, base, lora, G.to_dev(g32), None, out, 0, None)
+    G.assert_close("y", G.to_f64(out), I.to_f64(base_s) + ref_delta, tol)
+    # in place: out aliases base, inner aliases lora
+    b2, l2 = base.clone(), lora.clone()
+    D.dora_compose(desc, b2, l2, G.to_dev(g32), G.to_dev(gm1_32), b2, 0, l2)
+    G.assert_close("y in place", G.to_f64(b2), I.to_f64(base_s) + ref_delta_gm1, tol)
+    G.assert_close("inner in place", G.to_f64(l2), ref_inner, tol)
+    if dtype == "bf16":
+        # stricter than the tolerance: the delta is within bf16 rounding of the exact value
+        err = np.abs(G.to_f64(out) - (I.to_f64(base_s) + ref_delta))
+        assert np.max(err) <= 2.0 ** -8 * np.max(np.abs(I.to_f64(base_s) + ref_delta))
+
+
+def test_compose_forward_stable_near_unity():
+    # Sec. 3.1: with g within 1 +- 0.0015 the delta written in bf16 stays at the rounding floor of the
+    # delta itself (not of base), i.e. the (g-1) correction is not lost.
+    rng = np.random.default_rng(5)
+    tokens, d_out = 256, 1024
+    base_s = I.quantise(rng.standard_normal((tokens, d_out)), "bf16")
+    lora_s = I.quantise(np.zeros((tokens, d_out)), "bf16")
+    g32 = (1 + 0.0015 * rng.standard_normal(d_out)).astype(np.float32)
+    desc = D.make_desc(d_out, 8, 8, tokens, D.DORA_BF16, 1.0)
+    out = G.empty((tokens, d_out), "bf16")
+    D.dora_compose(desc, G.to_dev(base_s), G.to_dev(lora_s), G.to_dev(g32), None, out, 1, None)
+    ref = O.compose_delta(I.to_f64(base_s), I.to_f64(lora_s), g32.astype(np.float64), 1.0)
+    err = np.abs(G.to_f64(out) - ref)
+    assert np.all(err <= 2.0 ** -8 * np.abs(ref) + 1e-30)
+
+
+# ----------------------------------------------------------------------------- compose backward (a10)
+
+@pytest.mark.parametrize("dtype,tokens,d_out", [("f32", 64, 256), ("f32", 130, 100), ("bf16", 77, 200),
+                                               ("bf16", 300, 2056), ("bf16", 1030, 4096)])
+def test_compose_backward(dtype, tokens, d_out):
+    rng = np.random.default_rng(tokens * 3 + d_out)
+    dy_s = I.quantise(rng.standard_normal((tokens, d_out)), dtype)
+    inner_s = I.quantise(rng.standard_normal((tokens, d_out)), dtype)
+    g32 = (1 + 0.0015 * rng.standard_normal(d_out)).astype(np.float32)
+    c32 = (np.abs(rng.standard_normal(d_out)) + 0.5).astype(np.float32)
+    desc = D.make_desc(d_out, 8, 8, tokens, G.dtype_code(dtype), 1.5)
+    eps = 1e-6 if dtype == "bf16" else 1e-12
+    dz, dm = G.empty((tokens, d_out), dtype), G.empty_f32(d_out)
+    ws = G.workspace(desc, D.PHASE_COMPOSE_BACKWARD)
+    D.dora_compose_backward(desc, G.to_dev(dy_s), G.to_dev(inner_s), G.to_dev(g32), G.to_dev(c32), dz, dm, ws)
+    d_lora, d_base, ref_dm = O.grad_compose(I.to_f64(dy_s), I.to_f64(inner_s), g32.astype(np.float64),
+                                            c32.astype(np.float64), 1.5, eps)
+    tol = G.TOL[dtype]["tensor"]
+    G.assert_close("dz", G.to_f64(dz), d_base, tol)
+    np.testing.assert_allclose(d_lora, 1.5 * d_base, rtol=1e-14)  # the gradient reaching lora is s * dz
+    # dm is an fp32 sum of exact products: far tighter than the bf16 tolerance
+    G.assert_close("dm", G.to_f64(dm), ref_dm, 1e-5)
+    # frozen magnitude: dm skipped, inner / w_norm may be NULL
+    dz2 = G.empty((tokens, d_out), dtype)
+    D.dora_compose_backward(desc, G.to_dev(dy_s), None, G.to_dev(g32), None, dz2, None, None)
+    assert torch.equal(dz2.view(torch.uint8), dz.view(torch.uint8))
+
+
+# ----------------------------------------------------------------------------- contractions (a7, a8)
+
+@pytest.mark.parametrize("cfg", SMALL, ids=IDS)
+def test_project_and_delta(cfg):
+    mod = G.Module(cfg)
+    base = G.empty((cfg.tokens, cfg.d_out), cfg.dtype)
+    h = G.empty((cfg.tokens, cfg.r), cfg.dtype)
+    lora = G.empty((cfg.tokens, cfg.d_out), cfg.dtype)
+    D.dora_project(mod.desc, mod.x, mod.W, mod.A, mod.B, base, h, lora)
+    f = O.forward(**oracle_inputs(mod))
+    tol = G.TOL[cfg.dtype]["tensor"]
+    G.assert_close("base", G.to_f64(base), f["base"], tol)
+    G.assert_close("h", G.to_f64(h), f["h"], tol)
+    G.assert_close("lora", G.to_f64(lora), f["lora"], tol)
+    # delta through the library's own norm, g and compose
+    c = mod.norm()
+    g, gm1 = G.empty_f32(cfg.d_out), G.empty_f32(cfg.d_out)
+    D.dora_mag_scale(mod.desc, mod.m, c, g, gm1)
+    delta = G.empty((cfg.tokens, cfg.d_out), cfg.dtype)
+    D.dora_compose(mod.desc, base, lora, g, gm1, delta, 1, None)
+    G.assert_close("delta", G.to_f64(delta), f["delta"], tol)
+
+
+# ----------------------------------------------------------------------------- whole module
+
+@pytest.mark.parametrize("cfg", SMALL, ids=IDS)
+def test_forward_backward(cfg):
+    mod = G.Module(cfg)
+    oi = oracle_inputs(mod)
+    f = O.forward(**oi)
+    tol = G.TOL[cfg.dtype]["tensor"]
+    out = mod.forward()
+    G.assert_norm_close(G.to_f64(out["c"]), f["c"], G.TOL[cfg.dtype]["norm"])
+    G.assert_close("y", G.to_f64(out["y"]), f["y"], tol)
+    G.assert_close("inner", G.to_f64(out["inner"]), f["inner"], tol)
+    G.assert_close("h", G.to_f64(out["h"]), f["h"], tol)
+    # forward without saving anything gives the same y
+    out2 = mod.forward(save=False)
+    assert torch.equal(out2["y"].view(torch.uint8), out["y"].view(torch.uint8))
+    # forward with a supplied norm gives the same y
+    out3 = mod.forward(w_norm=out["c"], save=False)
+    assert torch.equal(out3["y"].view(torch.uint8), out["y"].view(torch.uint8))
+
+    b = O.backward(mod.f64("dy"), **oi)
+    for label, grads in (
+        ("saved", mod.backward(w_norm=out["c"], h=out["h"], inner=out["inner"])),
+        ("recompute", mod.backward()),
+    ):
+        for k in ("dx", "dA", "dB", "dm"):
+            G.assert_close(f"{k} [{label}]", G.to_f64(grads[k]), b[k], tol)
+    # frozen magnitude: same dx, dA, dB without inner
+    gf = mod.backward(w_norm=out["c"], h=out["h"], inner=None, want_dm=False)
+    ref = mod.backward(w_norm=out["c"], h=out["h"], inner=out["inner"])
+    for k in ("dx", "dA", "dB"):
+        assert torch.equal(gf[k].view(torch.uint8), ref[k].view(torch.uint8)), k
+
+
+def test_initial_state_is_identity():
+    # B = 0 and m = ||W||_row (DoRA's initialisation): y equals the base projection
+    cfg = cfg_bf16("init", 520, 392, 40, 300, seed=9)
+    inp = I.make_inputs(cfg)
+    inp["B"] = np.zeros_like(inp["B"])
+    inp["m"] = np.linalg.norm(I.to_f64(inp["W"]), axis=1).astype(np.float32)
+    mod = G.Module(cfg, inp)
+    out = mod.forward()
+    ref = mod.f64("x") @ mod.f64("W").T
+    G.assert_close("y", G.to_f64(out["y"]), ref, 2.0 ** -8)
+
+
+def test_runs_are_bitwise_reproducible():
+    cfg = cfg_bf16("bf16_ragged", 520, 392, 40, 300, seed=3)
+    mod = G.Module(cfg)
+    a, b = mod.forward(), mod.forward()
+    ga, gb = mod.backward(), mod.backward()
+    for k in ("y", "inner", "h", "c"):
+        assert torch.equal(a[k].view(torch.uint8), b[k].view(torch.uint8)), k
+    for k in ("dx", "dA", "dB", "dm"):
+        assert torch.equal(ga[k].view(torch.uint8), gb[k].view(torch.uint8)), k
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_zero_tokens(dtype):
+    mk = cfg_bf16 if dtype == "bf16" else cfg_f32
+    cfg = mk("empty", 136, 72, 16, 0, seed=10)
+    mod = G.Module(cfg)
+    out = mod.forward()
+    ref = O.dense_row_norm(mod.f64("W"), mod.f64("A"), mod.f64("B"), float(mod.inp["s"]))
+    G.assert_norm_close(G.to_f64(out["c"]), ref, G.TOL[dtype]["norm"])
+    g = mod.backward()
+    assert float(g["dA"].abs().max()) == 0.0 and float(g["dB"].abs().max()) == 0.0 and float(g["dm"].abs().max()) == 0.0
