@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Benchmark of the DoRA module hot path on one MI355X.
+
+A "step" is one pass of the whole path over one batch of synthetic input: dora_forward (factored
+norm, magnitude scale, the three contractions, compose, saving h / inner / w_norm) followed by
+dora_backward (compose backward with the fused dm reduction, dh, dx, dA, dB).  The workload is the
+headline configuration: d_out = d_in = 8192, r = 384, tokens = 8192, bf16 storage with fp32
+accumulation.  Inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line: tokens/s for the step, a roofline object for the dominant kernel (duration
+measured with HIP events recorded by the library on the launch stream during the timed steps), the
+same figures for every other kernel, and the fp64 CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
+
+
+def kernel_work(cfg):
+    """Algorithmic work per launch of each kernel: (flops, bytes), every operand touched once."""
+    T, do, di, r, e = cfg.tokens, cfg.d_out, cfg.d_in, cfg.r, 2
+    return {
+        "norm_cross_WAt": (2.0 * do * di * (r + 1), e * (do * di + r * di + do * r)),
+        "gram_AAt": (2.0 * r * r * di, e * r * di),
+        "gram_reduce": (0.0, 0.0),
+        "ba_sq_BGB": (2.0 * do * r * (2 * r + 1), e * (do * r + 2 * r * r)),
+        "norm_final": (0.0, 0.0),
+        "mag_scale": (0.0, 16.0 * do),
+        "gemm_base_xWt": (2.0 * T * do * di, e * (T * di + do * di + T * do)),
+        "gemm_h_xAt": (2.0 * T * r * di, e * (T * di + r * di + T * r)),
+        "gemm_lora_hBt": (2.0 * T * do * r, e * (T * r + do * r + T * do)),
+        "compose_fwd": (6.0 * T * do, e * 4.0 * T * do),       # reads base, lora; writes y, inner
+        "compose_bwd": (3.0 * T * do, e * 3.0 * T * do),       # reads dy, inner; writes dz
+        "dm_final": (0.0, 0.0),
+        "gemm_dh_dzB": (2.0 * T * r * do, e * (T * do + do * r + T * r)),
+        "gemm_dx": (2.0 * T * di * (do + r), e * (T * do + do * di + T * r + r * di + T * di)),
+        "gemm_dA": (2.0 * r * di * T, e * (T * r + T * di) + 4 * r * di),
+        "gemm_dB": (2.0 * do * r * T, e * (T * do + T * r) + 4 * do * r),
+    }
+
+
+HBM_BOUND = {"compose_fwd", "compose_bwd", "mag_scale"}
+
+
+def cpu_baseline(cfg, inp, sample_tokens):
+    """The fp64 oracle, as it stands, on the first `sample_tokens` tokens with the full weights."""
+    import numpy as np
+    from oracle import dora_oracle as O
+    from paper_2603_22276_amd import inputs as I
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:  # pragma: no cover
+        cores = os.cpu_count() or 1
+    n = min(sample_tokens, cfg.tokens)
+    W, A, B = I.to_f64(inp["W"]), I.to_f64(inp["A"]), I.to_f64(inp["B"])
+    x, dy = I.to_f64(inp["x"][:n]), I.to_f64(inp["dy"][:n])
+    m, s = inp["m"].astype(np.float64), float(inp["s"])
+    t0 = time.perf_counter()
+    f = O.forward(x, W, A, B, m, s, cfg.eps)
+    O.backward(dy, x, W, A, B, m, s, cfg.eps, c=f["c"])
+    dt = time.perf_counter() - t0
+    return {"value": n / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"fp64 numpy oracle, dense W+sBA norm + forward + backward, full weights, first {n} of "
+                      f"{cfg.tokens} tokens, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="C3", choices=["C2", "C3"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs the DoRA module on ONE GPU; --gpus N with N > 1 is not supported "
+              "(no collectives are part of the path).", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2603_22276_amd import binding as D
+    from paper_2603_22276_amd import inputs as I
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    import gpu_util as G
+
+    cfg = {"C2": I.C2, "C3": I.C3}[args.config]
+    inp = I.make_inputs(cfg)
+    mod = G.Module(cfg, inp)
+    desc = mod.desc
+    T, do, di, r = cfg.tokens, cfg.d_out, cfg.d_in, cfg.r
+    bf = torch.bfloat16
+    y = torch.empty((T, do), dtype=bf, device=G.DEV)
+    h = torch.empty((T, r), dtype=bf, device=G.DEV)
+    inner = torch.empty((T, do), dtype=bf, device=G.DEV)
+    c = torch.empty(do, dtype=torch.float32, device=G.DEV)
+    dx = torch.empty((T, di), dtype=bf, device=G.DEV)
+    dA = torch.empty((r, di), dtype=torch.float32, device=G.DEV)
+    dB = torch.empty((do, r), dtype=torch.float32, device=G.DEV)
+    dm = torch.empty(do, dtype=torch.float32, device=G.DEV)
+    ws_f = G.workspace(desc, D.PHASE_FORWARD)
+    ws_b = G.workspace(desc, D.PHASE_BACKWARD)
+
+    def step():
+        D.dora_forward(desc, mod.x, mod.W, mod.A, mod.B, mod.m, None, y, h, inner, c, ws_f)
+        D.dora_backward(desc, mod.dy, mod.x, mod.W, mod.A, mod.B, mod.m, c, h, inner, dx, dA, dB, dm, ws_b)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # timed region: exactly `steps` steps, per-kernel HIP events recorded by the library on the launch stream
+    D.dora_trace_reset()
+    D.dora_trace_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    D.dora_trace_enable(False)
+    D.dora_trace_collect()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # the same number of steps without the event pairs, to show what they cost
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t3 = time.perf_counter()
+    ms_untraced = (t3 - t2) * 1e3 / args.steps
+
+    work = kernel_work(cfg)
+    kernels = []
+    for kid in range(D.K_COUNT):
+        total_ms, n = D.dora_trace_get(kid)
+        if n == 0:
+            continue
+        name = D.dora_trace_name(kid)
+        avg_s = total_ms * 1e-3 / n
+        flops, nbytes = work[name]
+        hbm = name in HBM_BOUND
+        ach = (nbytes / avg_s / 1e9) if hbm else (flops / avg_s / 1e12)
+        peak = PEAK_HBM_GBS if hbm else PEAK_BF16_TFLOPS
+        kernels.append({"kernel": name, "launches_per_step": n / args.steps, "avg_us": avg_s * 1e6,
+                        "bound": "hbm" if hbm else "mfma", "achieved": ach, "peak": peak,
+                        "unit": "GB/s" if hbm else "TFLOP/s", "frac": ach / peak,
+                        "gbytes_per_s_algorithmic": nbytes / avg_s / 1e9})
+    dom = max(kernels, key=lambda k: k["avg_us"] * k["launches_per_step"])
+    roofline = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
+                "unit": dom["unit"], "frac": dom["frac"], "traffic": None}
+    mfma = [k for k in kernels if k["bound"] == "mfma" and work[k["kernel"]][0] > 0]
+    mfma_flops = sum(work[k["kernel"]][0] * k["launches_per_step"] for k in mfma)
+    mfma_time = sum(k["avg_us"] * 1e-6 * k["launches_per_step"] for k in mfma)
+
+    out = {
+        "metric": "DoRA fwd+bwd tokens/s at d_in=8192 r=384 bf16; %MFMA and %HBM peak",
+        "value": T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": cfg.name, "d_out": do, "d_in": di, "r": r, "tokens": T,
+                   "phase": "forward (saves h, inner, w_norm) + backward (dx, dA, dB, dm)"},
+        "roofline": roofline,
+        "mfma_frac_all_contractions": mfma_flops / mfma_time / 1e12 / PEAK_BF16_TFLOPS,
+        "hbm_frac_compose_fwd": next(k["frac"] for k in kernels if k["kernel"] == "compose_fwd"),
+        "hbm_frac_compose_bwd": next(k["frac"] for k in kernels if k["kernel"] == "compose_bwd"),
+        "ms_per_step_without_event_pairs": ms_untraced,
+        "workspace_bytes": {"norm": D.dora_workspace_bytes(desc, D.PHASE_NORM),
+                            "forward": D.dora_workspace_bytes(desc, D.PHASE_FORWARD),
+                            "backward": D.dora_workspace_bytes(desc, D.PHASE_BACKWARD),
+                            "dense_BA_temporary_avoided": do * di * 2},
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, inp, args.cpu_sample_tokens)
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -50,6 +50,42 @@ __device__ __forceinline__ int lds_off(int row, int k)
     return row * (BK * 2) + ((((k >> 3) ^ row) & (CPR - 1)) << 4) + ((k & 7) << 1);
 }
 
+// byte offset of element (row, k) in a [BK][ROWS] bf16 LDS tile (operand stored with K as the slow
+// axis).  16-byte chunks of 8 rows are XOR-swizzled by k so that the four k-rows one transposing read
+// touches fall into different bank groups.
+template <int ROWS>
+__device__ __forceinline__ int lds_off_ks(int row, int k)
+{
+    static_assert(ROWS >= 128, "swizzle needs at least 16 chunks per k-row");
+    return k * (ROWS * 2) + ((((row >> 3) ^ ((k & 3) << 2))) << 4) + ((row & 7) << 1);
+}
+
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
+
+// MFMA operand fragment for the 32 rows starting at `row0` and the 16 k starting at k16*16:
+// lane l gets row row0 + (l & 31), k = k16*16 + 8*(l >> 5) + 0..7.
+template <int ROWS, bool KCONTIG>
+__device__ __forceinline__ bf16x8_t load_frag(const char* tile, int row0, int k16, int lane)
+{
+    if (KCONTIG) {
+        return *reinterpret_cast<const bf16x8_t*>(tile + lds_off(row0 + (lane & 31), k16 * 16 + (lane >> 5) * 8));
+    } else {
+        // ds_read_b64_tr_b16: inside each block of 16 lanes, lane i receives element (i & 3) of the
+        // 8 bytes addressed by lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12.  Lane L therefore points at
+        // k-row (L & 15) / 4 and rows 4*(L & 3) .. +3 of its block; blocks 1 and 3 sit 16 rows further,
+        // blocks 2 and 3 eight k further.
+        const int row = row0 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
+        const int k = k16 * 16 + (lane >> 5) * 8 + ((lane & 15) >> 2);
+        typedef s16x4_t __attribute__((address_space(3))) * lds_ptr_t;
+        const char* p0 = tile + lds_off_ks<ROWS>(row, k);
+        s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p0));
+        s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p0 + 4 * ROWS * 2));  // k + 4: same swizzle
+        s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(bf16x8_t, v);
+    }
+}
+
 template <int ROWS, int NL, int THREADS, bool KCONTIG>
 struct OperandLoader {
     // Loads one [ROWS x BK] operand tile into registers; invalid chunks read as zero.
@@ -79,14 +115,10 @@ struct OperandLoader {
                 int row = c / CPR, k = (c % CPR) * 8;
                 *reinterpret_cast<uint4*>(tile + lds_off(row, k)) = reg[i];
             } else {
-                // the chunk holds 8 consecutive rows at one k: scatter them (transposing store)
-                int k = c / (ROWS / 8), row = (c % (ROWS / 8)) * 8;
-                uint32_t w[4] = {reg[i].x, reg[i].y, reg[i].z, reg[i].w};
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    uint16_t v = (uint16_t)((e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xffffu));
-                    *reinterpret_cast<uint16_t*>(tile + lds_off(row + e, k)) = v;
-                }
+                // the chunk holds 8 consecutive rows at one k: keep it as loaded, [k][rows] in LDS;
+                // the transposing LDS read below turns it into MFMA operand order
+                int k = c / (ROWS / 8), rc = c % (ROWS / 8);
+                *reinterpret_cast<uint4*>(tile + lds_off_ks<ROWS>(rc * 8, k)) = reg[i];
             }
         }
     }
@@ -187,13 +219,12 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmArgs p)
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
             bf16x8_t af[MT], bfr[NT];
-            const int k = kk * 16 + lh * 8;
 #pragma unroll
             for (int i = 0; i < MT; ++i)
-                af[i] = *reinterpret_cast<const bf16x8_t*>(sa + lds_off(wm0 + i * 32 + l32, k));
+                af[i] = load_frag<BM, A_KC>(sa, wm0 + i * 32, kk, lane);
 #pragma unroll
             for (int j = 0; j < NT; ++j)
-                bfr[j] = *reinterpret_cast<const bf16x8_t*>(sb + lds_off(wn0 + j * 32 + l32, k));
+                bfr[j] = load_frag<BN, B_KC>(sb, wn0 + j * 32, kk, lane);
 #pragma unroll
             for (int i = 0; i < MT; ++i)
 #pragma unroll
