@@ -44,10 +44,12 @@ struct Tile {
 typedef Tile<256, 256, 2, 4> TileBig;   // 512 threads, 128 KB of LDS, 128 accumulator registers per lane
 typedef Tile<128, 128, 2, 2> TileMed;   // 256 threads,  64 KB of LDS, two workgroups fit a CU
 
-// byte offset of element (row, k) in a swizzled [rows][BK] bf16 LDS tile
+// byte offset of element (row, k) in a swizzled [rows][BK] bf16 LDS tile.  The LDS has 64 banks of
+// 4 bytes and serves a 16-byte-per-lane read 16 lanes at a time; a row is 128 bytes, so the 16 rows
+// of one such group cover every bank exactly once when the chunk index is XORed with row/2.
 __device__ __forceinline__ int lds_off(int row, int k)
 {
-    return row * (BK * 2) + ((((k >> 3) ^ row) & (CPR - 1)) << 4) + ((k & 7) << 1);
+    return row * (BK * 2) + ((((k >> 3) ^ (row >> 1)) & (CPR - 1)) << 4) + ((k & 7) << 1);
 }
 
 // byte offset of element (row, k) in a [BK][ROWS] bf16 LDS tile (operand stored with K as the slow
@@ -61,6 +63,7 @@ __device__ __forceinline__ int lds_off_ks(int row, int k)
 }
 
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x8_t __attribute__((ext_vector_type(8)));
 
 // MFMA operand fragment for the 32 rows starting at `row0` and the 16 k starting at k16*16:
@@ -88,9 +91,16 @@ __device__ __forceinline__ bf16x8_t load_frag(const char* tile, int row0, int k1
 
 template <int ROWS, int NL, int THREADS, bool KCONTIG>
 struct OperandLoader {
-    // Loads one [ROWS x BK] operand tile into registers; invalid chunks read as zero.
-    static __device__ __forceinline__ void gload(uint4 (&reg)[NL], const bf16_t* __restrict__ base, int64_t ld,
-                                                 int row0, int rows, int k0, int K, int tid)
+    // Global loads go through a buffer descriptor: an offset at or beyond num_records reads as zero,
+    // which covers rows past the end of the operand; rows or k that are out of range for other
+    // reasons get the offset 0xFFFFFFFF.  The K advance travels in the scalar offset.
+    static __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const bf16_t* base, int64_t ld, int rows, int K)
+    {
+        int64_t elems = KCONTIG ? ((int64_t)(rows - 1) * ld + K) : ((int64_t)(K - 1) * ld + rows);
+        if (rows <= 0 || K <= 0) elems = 0;
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(base), 0, (int)(uint32_t)(elems * 2), 0x00020000);
+    }
+    static __device__ __forceinline__ void offsets(uint32_t (&vo)[NL], int64_t ld, int row0, int rows, int tid)
     {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
@@ -98,12 +108,26 @@ struct OperandLoader {
             int row, k;
             if (KCONTIG) { row = c / CPR; k = (c % CPR) * 8; }
             else { k = c / (ROWS / 8); row = (c % (ROWS / 8)) * 8; }
-            int grow = row0 + row, gk = k0 + k;
-            bool ok = (grow < rows) && (gk < K);
-            const bf16_t* p = KCONTIG ? base + (int64_t)grow * ld + gk : base + (int64_t)gk * ld + grow;
-            uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (ok) v = *reinterpret_cast<const uint4*>(p);
-            reg[i] = v;
+            int grow = row0 + row;
+            uint32_t off = KCONTIG ? (uint32_t)(((int64_t)grow * ld + k) * 2) : (uint32_t)(((int64_t)k * ld + grow) * 2);
+            vo[i] = (grow < rows) ? off : 0xFFFFFFFFu;
+        }
+    }
+    template <bool TAIL>
+    static __device__ __forceinline__ void gload(uint4 (&reg)[NL], __amdgpu_buffer_rsrc_t rs, const uint32_t (&vo)[NL],
+                                                 int64_t ld, int k0, int K, int tid)
+    {
+        const uint32_t so = KCONTIG ? (uint32_t)(k0 * 2) : (uint32_t)((int64_t)k0 * ld * 2);
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            uint32_t off = vo[i];
+            if (TAIL) {
+                int c = tid + i * THREADS;
+                int k = KCONTIG ? (c % CPR) * 8 : c / (ROWS / 8);
+                if (k0 + k >= K) off = 0xFFFFFFFFu;
+            }
+            u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rs, off, so, 0);
+            reg[i] = make_uint4(v.x, v.y, v.z, v.w);
         }
     }
     static __device__ __forceinline__ void lstore(const uint4 (&reg)[NL], char* tile, int tid)
@@ -191,66 +215,113 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmArgs p)
     typedef OperandLoader<BM, T::NLA, THREADS, A_KC> LA;
     typedef OperandLoader<BN, T::NLB, THREADS, B_KC> LB;
     uint4 ra[T::NLA], rb[T::NLB];
+    uint32_t voa[T::NLA], vob[T::NLB];   // per-thread byte offsets into the current segment's operands
+    __amdgpu_buffer_rsrc_t rsa, rsb;     // buffer descriptors of the current segment's operands
+    int64_t lda_cur = 0, ldb_cur = 0;
+    int K_cur = 0;
 
+    auto set_segment = [&](int s) {
+        const GemmSeg& sg = p.seg[s];
+        lda_cur = sg.lda; ldb_cur = sg.ldb; K_cur = sg.K;
+        rsa = LA::make_rsrc(sg.a, sg.lda, p.M, sg.K);
+        rsb = LB::make_rsrc(sg.b, sg.ldb, p.N, sg.K);
+        LA::offsets(voa, sg.lda, m0, p.M, tid);
+        LB::offsets(vob, sg.ldb, n0, p.N, tid);
+    };
+    int seg_loaded = -1;
     auto gload = [&](int t) {
         const int s = (t >= kt0_total) ? 1 : 0;
+        if (s != seg_loaded) { set_segment(s); seg_loaded = s; }
         const int k0 = (s ? t - kt0_total : t) * BK;
-        const GemmSeg& sg = p.seg[s];
-        LA::gload(ra, sg.a, sg.lda, m0, p.M, k0, sg.K, tid);
-        LB::gload(rb, sg.b, sg.ldb, n0, p.N, k0, sg.K, tid);
+        if (k0 + BK <= K_cur) {
+            LA::template gload<false>(ra, rsa, voa, lda_cur, k0, K_cur, tid);
+            LB::template gload<false>(rb, rsb, vob, ldb_cur, k0, K_cur, tid);
+        } else {
+            LA::template gload<true>(ra, rsa, voa, lda_cur, k0, K_cur, tid);
+            LB::template gload<true>(rb, rsb, vob, ldb_cur, k0, K_cur, tid);
+        }
     };
     auto lstore = [&](int stage) {
         char* st = smem + stage * T::STAGE_BYTES;
         LA::lstore(ra, st, tid);
         LB::lstore(rb, st + T::A_BYTES, tid);
     };
+    auto frags = [&](bf16x8_t (&af)[MT], bf16x8_t (&bfr)[NT], int stage, int kk) {
+        const char* sa = smem + stage * T::STAGE_BYTES;
+        const char* sb = sa + T::A_BYTES;
+#pragma unroll
+        for (int i = 0; i < MT; ++i) af[i] = load_frag<BM, A_KC>(sa, wm0 + i * 32, kk, lane);
+#pragma unroll
+        for (int j = 0; j < NT; ++j) bfr[j] = load_frag<BN, B_KC>(sb, wn0 + j * 32, kk, lane);
+    };
+    auto mma = [&](const bf16x8_t (&af)[MT], const bf16x8_t (&bfr)[NT], int kk) {
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+        if (EPI == EPI_ROWDOT) {
+            // base term of Eq. 2: sum of squares of the M-side rows, taken from the fragments
+            // already in registers; the waves along N share the K steps between them
+            if (want_bsq && (kk % T::WGN) == wn) {
+#pragma unroll
+                for (int i = 0; i < MT; ++i) {
+                    uint4 u = __builtin_bit_cast(uint4, af[i]);
+                    uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        float lo = bf16_lo(w[e]), hi = bf16_hi(w[e]);
+                        bsq[i] = fmaf(lo, lo, bsq[i]);
+                        bsq[i] = fmaf(hi, hi, bsq[i]);
+                    }
+                }
+            }
+        }
+    };
 
+    // Software pipeline.  Per K tile (4 steps of 16): the fragments of step kk+1 are read from LDS
+    // while the MFMAs of step kk run; the next tile is written to the other LDS stage and the
+    // workgroup barrier is taken BEFORE the last step's MFMAs, so that those MFMAs cover the
+    // latency of the first fragment reads of the next tile.  Global loads run one tile ahead in
+    // registers.
+    bf16x8_t a0[MT], b0[NT], a1[MT], b1[NT];
     if (t_begin < t_end) {
         gload(t_begin);
         lstore(0);
     }
     __syncthreads();
-
+    if (t_begin < t_end) {
+        frags(a0, b0, 0, 0);
+        if (t_begin + 1 < t_end) gload(t_begin + 1);
+    }
     for (int t = t_begin; t < t_end; ++t) {
         const int stage = (t - t_begin) & 1;
-        if (t + 1 < t_end) gload(t + 1);
-        const char* sa = smem + stage * T::STAGE_BYTES;
-        const char* sb = sa + T::A_BYTES;
-#pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            bf16x8_t af[MT], bfr[NT];
-#pragma unroll
-            for (int i = 0; i < MT; ++i)
-                af[i] = load_frag<BM, A_KC>(sa, wm0 + i * 32, kk, lane);
-#pragma unroll
-            for (int j = 0; j < NT; ++j)
-                bfr[j] = load_frag<BN, B_KC>(sb, wn0 + j * 32, kk, lane);
-#pragma unroll
-            for (int i = 0; i < MT; ++i)
-#pragma unroll
-                for (int j = 0; j < NT; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
-            if (EPI == EPI_ROWDOT) {
-                // base term of Eq. 2: sum of squares of the M-side rows, taken from the fragments
-                // already in registers; the waves along N share the K steps between them
-                if (want_bsq && (kk % T::WGN) == wn) {
-#pragma unroll
-                    for (int i = 0; i < MT; ++i) {
-                        uint4 u = __builtin_bit_cast(uint4, af[i]);
-                        uint32_t w[4] = {u.x, u.y, u.z, u.w};
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            float lo = bf16_lo(w[e]), hi = bf16_hi(w[e]);
-                            bsq[i] = fmaf(lo, lo, bsq[i]);
-                            bsq[i] = fmaf(hi, hi, bsq[i]);
-                        }
-                    }
-                }
-            }
-        }
-        if (t + 1 < t_end) lstore(stage ^ 1);
+        const bool has_next = t + 1 < t_end;
+        // sched_barrier(0) pins the order: this step's LDS reads are issued first, then the MFMAs
+        // of the previous step's fragments run while those reads are in flight
+        frags(a1, b1, stage, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(a0, b0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        frags(a0, b0, stage, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(a1, b1, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        frags(a1, b1, stage, 3);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(a0, b0, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        if (has_next) lstore(stage ^ 1);
         __syncthreads();
+        if (has_next) {
+            frags(a0, b0, stage ^ 1, 0);
+            if (t + 2 < t_end) gload(t + 2);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        mma(a1, b1, 3);
+        __builtin_amdgcn_sched_barrier(0);
     }
+    __syncthreads();
 
     // ------------------------------------------------------------------------------ epilogues
     if (EPI == EPI_ROWDOT) {
