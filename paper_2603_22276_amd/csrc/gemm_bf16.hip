@@ -7,9 +7,11 @@
 // (both K-strided), and the factored-norm products of Sec. 2: U = W A^T with the row-dot epilogue
 // of Eq. 3 (U never leaves registers), G = A A^T (Eq. 4, split-K partials), and rowdot(B, B G).
 //
-// Structure (per workgroup): a BM x BN tile of C, K walked in steps of 64.  Global -> registers ->
-// LDS double buffer (XOR-swizzled 16-byte chunks so MFMA operand reads spread over the banks),
-// v_mfma_f32_32x32x16_bf16 on 64-wide wavefronts, each wave owning a (BM/WGM) x (BN/WGN) sub-tile.
+// Structure (per workgroup): a BM x BN tile of C; K is walked in steps of 32 through a ring of four
+// LDS buffers that the global loads fill directly (buffer_load ... lds, 16 bytes per lane, no
+// register staging), three steps ahead of the MFMAs.  v_mfma_f32_32x32x16_bf16 on 64-wide
+// wavefronts, each wave owning a (BM/WGM) x (BN/WGN) sub-tile; operand fragments are double
+// buffered in registers so the LDS reads of one k-step overlap the MFMAs of the previous one.
 // The N-side fragment is fed as the MFMA's first operand so that every lane ends up holding four
 // consecutive n for one m, which makes the epilogue's stores and row-dots vector-friendly.
 // Workgroup ids are remapped so that each of the 8 XCDs (own L2 each) works on a compact block of
@@ -19,8 +21,9 @@
 namespace dora {
 namespace {
 
-constexpr int BK = 64;          // K step per LDS stage (elements)
-constexpr int CPR = BK / 8;     // 16-byte chunks per LDS row
+constexpr int BK = 32;          // K step per LDS buffer (elements)
+constexpr int CPR = BK / 8;     // 16-byte chunks per K-contiguous LDS row
+constexpr int STAGES = 4;       // LDS ring depth
 constexpr int NUM_XCD = 8;
 constexpr int GROUP_M = 8;
 
@@ -32,11 +35,11 @@ struct Tile {
     static constexpr int MT = WM / 32, NT = WN / 32;
     static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-    static constexpr int NLA = BM * CPR / THREADS;  // 16-byte global loads per thread per stage, M side
+    static constexpr int NLA = BM * CPR / THREADS;  // 16-byte global loads per thread per K step, M side
     static constexpr int NLB = BN * CPR / THREADS;
     static constexpr int EPI_BYTES_PER_WAVE = 32 * (WN * 4 + 16);
-    static constexpr int LDS_BYTES =
-        (2 * STAGE_BYTES > WAVES * EPI_BYTES_PER_WAVE) ? 2 * STAGE_BYTES : WAVES * EPI_BYTES_PER_WAVE;
+    static constexpr int LDS_BYTES = (STAGES * STAGE_BYTES > WAVES * EPI_BYTES_PER_WAVE) ? STAGES * STAGE_BYTES
+                                                                                        : WAVES * EPI_BYTES_PER_WAVE;
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
     static_assert((BM * CPR) % THREADS == 0 && (BN * CPR) % THREADS == 0, "load plan must divide evenly");
 };
@@ -44,27 +47,29 @@ struct Tile {
 typedef Tile<256, 256, 2, 4> TileBig;   // 512 threads, 128 KB of LDS, 128 accumulator registers per lane
 typedef Tile<128, 128, 2, 2> TileMed;   // 256 threads,  64 KB of LDS, two workgroups fit a CU
 
-// byte offset of element (row, k) in a swizzled [rows][BK] bf16 LDS tile.  The LDS has 64 banks of
-// 4 bytes and serves a 16-byte-per-lane read 16 lanes at a time; a row is 128 bytes, so the 16 rows
-// of one such group cover every bank exactly once when the chunk index is XORed with row/2.
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
+typedef uint64_t u64x1_t;
+typedef uint64_t u64x2_t __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) void* lds_void_ptr_t;
+
+// The LDS has 64 banks of 4 bytes and serves a 16-byte-per-lane access 16 lanes at a time, so 16
+// consecutive lanes must touch 16 different 16-byte slots modulo 256 bytes.
+//
+// K-contiguous operand: [rows][BK] bf16, 64 bytes per row, chunk index XORed with row/4: the 16 rows
+// one group of lanes reads (same logical chunk) then cover all 16 slots.
 __device__ __forceinline__ int lds_off(int row, int k)
 {
-    return row * (BK * 2) + ((((k >> 3) ^ (row >> 1)) & (CPR - 1)) << 4) + ((k & 7) << 1);
+    return row * (BK * 2) + ((((k >> 3) ^ (row >> 2)) & (CPR - 1)) << 4) + ((k & 7) << 1);
 }
-
-// byte offset of element (row, k) in a [BK][ROWS] bf16 LDS tile (operand stored with K as the slow
-// axis).  16-byte chunks of 8 rows are XOR-swizzled by k so that the four k-rows one transposing read
-// touches fall into different bank groups.
+// K-strided operand: kept as loaded, [BK][ROWS] bf16; chunks of 8 rows XORed with 4*(k mod 4) so the
+// four k-rows one transposing read touches fall into different slots.
 template <int ROWS>
 __device__ __forceinline__ int lds_off_ks(int row, int k)
 {
     static_assert(ROWS >= 128, "swizzle needs at least 16 chunks per k-row");
     return k * (ROWS * 2) + ((((row >> 3) ^ ((k & 3) << 2))) << 4) + ((row & 7) << 1);
 }
-
-typedef short s16x4_t __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
-typedef short s16x8_t __attribute__((ext_vector_type(8)));
 
 // MFMA operand fragment for the 32 rows starting at `row0` and the 16 k starting at k16*16:
 // lane l gets row row0 + (l & 31), k = k16*16 + 8*(l >> 5) + 0..7.
@@ -80,70 +85,68 @@ __device__ __forceinline__ bf16x8_t load_frag(const char* tile, int row0, int k1
         // blocks 2 and 3 eight k further.
         const int row = row0 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
         const int k = k16 * 16 + (lane >> 5) * 8 + ((lane & 15) >> 2);
-        typedef s16x4_t __attribute__((address_space(3))) * lds_ptr_t;
-        const char* p0 = tile + lds_off_ks<ROWS>(row, k);
-        s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p0));
-        s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p0 + 4 * ROWS * 2));  // k + 4: same swizzle
-        s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        // Issued as inline assembly: the compiler otherwise makes this read wait for every global
+        // load still in flight to the other ring slots.  The caller waits on lgkmcnt before use.
+        typedef __attribute__((address_space(3))) const char* lds_cptr_t;
+        const uint32_t addr = (uint32_t)(uintptr_t)(lds_cptr_t)(tile + lds_off_ks<ROWS>(row, k));
+        u64x1_t lo, hi;
+        asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(addr));
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(addr), "n"(4 * ROWS * 2));  // k + 4: same swizzle
+        u64x2_t v = {lo, hi};
         return __builtin_bit_cast(bf16x8_t, v);
     }
 }
 
-template <int ROWS, int NL, int THREADS, bool KCONTIG>
+// Global -> LDS for one [ROWS x BK] operand tile.  Each wave-wide load instruction fills 1 KB of
+// contiguous LDS (lane i lands at byte 16*i of it), so lane i fetches from global memory whatever
+// belongs at that position of the swizzled tile.  Loads go through a buffer descriptor: an offset at
+// or beyond num_records yields zeros, which covers rows past the end of the operand; rows or k out
+// of range for other reasons get the offset 0xFFFFFFFF.  The K advance travels in the scalar offset.
+template <int ROWS, int NL, int WAVES, bool KCONTIG>
 struct OperandLoader {
-    // Global loads go through a buffer descriptor: an offset at or beyond num_records reads as zero,
-    // which covers rows past the end of the operand; rows or k that are out of range for other
-    // reasons get the offset 0xFFFFFFFF.  The K advance travels in the scalar offset.
     static __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const bf16_t* base, int64_t ld, int rows, int K)
     {
         int64_t elems = KCONTIG ? ((int64_t)(rows - 1) * ld + K) : ((int64_t)(K - 1) * ld + rows);
         if (rows <= 0 || K <= 0) elems = 0;
         return __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(base), 0, (int)(uint32_t)(elems * 2), 0x00020000);
     }
-    static __device__ __forceinline__ void offsets(uint32_t (&vo)[NL], int64_t ld, int row0, int rows, int tid)
+    // tile-local (row, k) of the chunk that load i of this lane brings in
+    static __device__ __forceinline__ void chunk_of(int i, int wave, int lane, int& row, int& k)
+    {
+        const int pos = (i * WAVES + wave) * 64 + lane;  // chunk position in the LDS tile
+        if (KCONTIG) {
+            row = pos / CPR;
+            k = (((pos % CPR) ^ (row >> 2)) & (CPR - 1)) * 8;
+        } else {
+            k = pos / (ROWS / 8);
+            row = ((pos % (ROWS / 8)) ^ ((k & 3) << 2)) * 8;
+        }
+    }
+    static __device__ __forceinline__ void offsets(uint32_t (&vo)[NL], int64_t ld, int row0, int rows, int wave, int lane)
     {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
-            int c = tid + i * THREADS;
             int row, k;
-            if (KCONTIG) { row = c / CPR; k = (c % CPR) * 8; }
-            else { k = c / (ROWS / 8); row = (c % (ROWS / 8)) * 8; }
+            chunk_of(i, wave, lane, row, k);
             int grow = row0 + row;
             uint32_t off = KCONTIG ? (uint32_t)(((int64_t)grow * ld + k) * 2) : (uint32_t)(((int64_t)k * ld + grow) * 2);
             vo[i] = (grow < rows) ? off : 0xFFFFFFFFu;
         }
     }
     template <bool TAIL>
-    static __device__ __forceinline__ void gload(uint4 (&reg)[NL], __amdgpu_buffer_rsrc_t rs, const uint32_t (&vo)[NL],
-                                                 int64_t ld, int k0, int K, int tid)
+    static __device__ __forceinline__ void issue(char* tile, __amdgpu_buffer_rsrc_t rs, const uint32_t (&vo)[NL],
+                                                 int64_t ld, int k0, int K, int wave, int lane)
     {
         const uint32_t so = KCONTIG ? (uint32_t)(k0 * 2) : (uint32_t)((int64_t)k0 * ld * 2);
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             uint32_t off = vo[i];
             if (TAIL) {
-                int c = tid + i * THREADS;
-                int k = KCONTIG ? (c % CPR) * 8 : c / (ROWS / 8);
+                int row, k;
+                chunk_of(i, wave, lane, row, k);
                 if (k0 + k >= K) off = 0xFFFFFFFFu;
             }
-            u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rs, off, so, 0);
-            reg[i] = make_uint4(v.x, v.y, v.z, v.w);
-        }
-    }
-    static __device__ __forceinline__ void lstore(const uint4 (&reg)[NL], char* tile, int tid)
-    {
-#pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            int c = tid + i * THREADS;
-            if (KCONTIG) {
-                int row = c / CPR, k = (c % CPR) * 8;
-                *reinterpret_cast<uint4*>(tile + lds_off(row, k)) = reg[i];
-            } else {
-                // the chunk holds 8 consecutive rows at one k: keep it as loaded, [k][rows] in LDS;
-                // the transposing LDS read below turns it into MFMA operand order
-                int k = c / (ROWS / 8), rc = c % (ROWS / 8);
-                *reinterpret_cast<uint4*>(tile + lds_off_ks<ROWS>(rc * 8, k)) = reg[i];
-            }
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_ptr_t)(tile + (i * WAVES + wave) * 1024), 16, off, so, 0, 0);
         }
     }
 };
@@ -173,14 +176,32 @@ __device__ __forceinline__ TileCoord map_tile(int wg, int tiles_m, int tiles_n, 
     return t;
 }
 
+// s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt in bits 3:0 and
+// 15:14, expcnt 6:4 and lgkmcnt 11:8 left at their maxima)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+}
+
+template <int N>
+__device__ __forceinline__ void wait_lgkmcnt()
+{
+    static_assert(N >= 0 && N <= 15, "lgkmcnt is a 4-bit counter");
+    __builtin_amdgcn_s_waitcnt(0xC07F | (N << 8));
+}
+
 template <class T, bool A_KC, bool B_KC, int EPI>
 __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmArgs p)
 {
-    constexpr int BM = T::BM, BN = T::BN, MT = T::MT, NT = T::NT, THREADS = T::THREADS;
-    __shared__ __attribute__((aligned(16))) char smem[T::LDS_BYTES];
+    constexpr int BM = T::BM, BN = T::BN, MT = T::MT, NT = T::NT;
+    constexpr int FRAG_OPS = MT * (A_KC ? 1 : 2) + NT * (B_KC ? 1 : 2);  // LDS reads per k-step of 16
+    constexpr int LPT = T::NLA + T::NLB;  // load instructions per K step per lane
+    __shared__ __attribute__((aligned(1024))) char smem[T::LDS_BYTES];
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, lh = lane >> 5;
     const int wm = wave / T::WGN, wn = wave % T::WGN;
     const int wm0 = wm * T::WM, wn0 = wn * T::WN;
@@ -189,7 +210,7 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmArgs p)
     const TileCoord tc = map_tile(blockIdx.x, tiles_m, tiles_n, p.ksplit);
     const int m0 = tc.tm * BM, n0 = tc.tn * BN;
 
-    // flattened K-tile schedule over the segments; split-K slices segment 0 only
+    // flattened K-step schedule over the segments; split-K slices segment 0 only
     const int kt0_total = (p.seg[0].K + BK - 1) / BK;
     const int kt1_total = (p.nseg > 1) ? (p.seg[1].K + BK - 1) / BK : 0;
     int t_begin = 0, t_end = kt0_total + kt1_total;
@@ -199,6 +220,7 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmArgs p)
         t_end = t_begin + per < kt0_total ? t_begin + per : kt0_total;
         if (t_end < t_begin) t_end = t_begin;
     }
+    const int nsteps = t_end - t_begin;
 
     f32x16_t acc[MT][NT];
 #pragma unroll
@@ -212,42 +234,38 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmArgs p)
     for (int i = 0; i < MT; ++i) bsq[i] = 0.f;
     const bool want_bsq = (EPI == EPI_ROWDOT) && (p.base_sq_partial != nullptr) && (tc.tn == 0);
 
-    typedef OperandLoader<BM, T::NLA, THREADS, A_KC> LA;
-    typedef OperandLoader<BN, T::NLB, THREADS, B_KC> LB;
-    uint4 ra[T::NLA], rb[T::NLB];
-    uint32_t voa[T::NLA], vob[T::NLB];   // per-thread byte offsets into the current segment's operands
+    typedef OperandLoader<BM, T::NLA, T::WAVES, A_KC> LA;
+    typedef OperandLoader<BN, T::NLB, T::WAVES, B_KC> LB;
+    uint32_t voa[T::NLA], vob[T::NLB];   // per-lane byte offsets into the current segment's operands
     __amdgpu_buffer_rsrc_t rsa, rsb;     // buffer descriptors of the current segment's operands
     int64_t lda_cur = 0, ldb_cur = 0;
     int K_cur = 0;
-
-    auto set_segment = [&](int s) {
-        const GemmSeg& sg = p.seg[s];
-        lda_cur = sg.lda; ldb_cur = sg.ldb; K_cur = sg.K;
-        rsa = LA::make_rsrc(sg.a, sg.lda, p.M, sg.K);
-        rsb = LB::make_rsrc(sg.b, sg.ldb, p.N, sg.K);
-        LA::offsets(voa, sg.lda, m0, p.M, tid);
-        LB::offsets(vob, sg.ldb, n0, p.N, tid);
-    };
     int seg_loaded = -1;
-    auto gload = [&](int t) {
+
+    // issue the global -> LDS loads of K step t (absolute index) into ring slot `slot`
+    auto issue = [&](int t, int slot) {
         const int s = (t >= kt0_total) ? 1 : 0;
-        if (s != seg_loaded) { set_segment(s); seg_loaded = s; }
+        if (s != seg_loaded) {
+            const GemmSeg& sg = p.seg[s];
+            lda_cur = sg.lda; ldb_cur = sg.ldb; K_cur = sg.K;
+            rsa = LA::make_rsrc(sg.a, sg.lda, p.M, sg.K);
+            rsb = LB::make_rsrc(sg.b, sg.ldb, p.N, sg.K);
+            LA::offsets(voa, sg.lda, m0, p.M, wave, lane);
+            LB::offsets(vob, sg.ldb, n0, p.N, wave, lane);
+            seg_loaded = s;
+        }
         const int k0 = (s ? t - kt0_total : t) * BK;
+        char* st = smem + slot * T::STAGE_BYTES;
         if (k0 + BK <= K_cur) {
-            LA::template gload<false>(ra, rsa, voa, lda_cur, k0, K_cur, tid);
-            LB::template gload<false>(rb, rsb, vob, ldb_cur, k0, K_cur, tid);
+            LA::template issue<false>(st, rsa, voa, lda_cur, k0, K_cur, wave, lane);
+            LB::template issue<false>(st + T::A_BYTES, rsb, vob, ldb_cur, k0, K_cur, wave, lane);
         } else {
-            LA::template gload<true>(ra, rsa, voa, lda_cur, k0, K_cur, tid);
-            LB::template gload<true>(rb, rsb, vob, ldb_cur, k0, K_cur, tid);
+            LA::template issue<true>(st, rsa, voa, lda_cur, k0, K_cur, wave, lane);
+            LB::template issue<true>(st + T::A_BYTES, rsb, vob, ldb_cur, k0, K_cur, wave, lane);
         }
     };
-    auto lstore = [&](int stage) {
-        char* st = smem + stage * T::STAGE_BYTES;
-        LA::lstore(ra, st, tid);
-        LB::lstore(rb, st + T::A_BYTES, tid);
-    };
-    auto frags = [&](bf16x8_t (&af)[MT], bf16x8_t (&bfr)[NT], int stage, int kk) {
-        const char* sa = smem + stage * T::STAGE_BYTES;
+    auto frags = [&](bf16x8_t (&af)[MT], bf16x8_t (&bfr)[NT], int slot, int kk) {
+        const char* sa = smem + slot * T::STAGE_BYTES;
         const char* sb = sa + T::A_BYTES;
 #pragma unroll
         for (int i = 0; i < MT; ++i) af[i] = load_frag<BM, A_KC>(sa, wm0 + i * 32, kk, lane);
@@ -278,49 +296,48 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmArgs p)
             }
         }
     };
+    // wait until the loads of the oldest outstanding K step have landed, given how many younger
+    // steps are in flight behind it
+    auto wait_oldest = [&](int younger) {
+        if (younger >= 2) wait_vmcnt<2 * LPT>();
+        else if (younger == 1) wait_vmcnt<LPT>();
+        else wait_vmcnt<0>();
+    };
 
-    // Software pipeline.  Per K tile (4 steps of 16): the fragments of step kk+1 are read from LDS
-    // while the MFMAs of step kk run; the next tile is written to the other LDS stage and the
-    // workgroup barrier is taken BEFORE the last step's MFMAs, so that those MFMAs cover the
-    // latency of the first fragment reads of the next tile.  Global loads run one tile ahead in
-    // registers.
+    // Pipeline.  Ring slot u % 4 holds K step u.  Up to three steps are in flight behind the one
+    // being multiplied.  Per step: wait for its data, workgroup barrier (which also says every wave
+    // is done reading step u-1), refill the slot step u-1 occupied with step u+3, read the first
+    // fragments of step u, and only then run the last MFMAs of step u-1 - they cover the latency
+    // of those fragment reads.
     bf16x8_t a0[MT], b0[NT], a1[MT], b1[NT];
-    if (t_begin < t_end) {
-        gload(t_begin);
-        lstore(0);
-    }
-    __syncthreads();
-    if (t_begin < t_end) {
-        frags(a0, b0, 0, 0);
-        if (t_begin + 1 < t_end) gload(t_begin + 1);
-    }
-    for (int t = t_begin; t < t_end; ++t) {
-        const int stage = (t - t_begin) & 1;
-        const bool has_next = t + 1 < t_end;
-        // sched_barrier(0) pins the order: this step's LDS reads are issued first, then the MFMAs
-        // of the previous step's fragments run while those reads are in flight
-        frags(a1, b1, stage, 1);
+#pragma unroll
+    for (int u = 0; u < STAGES - 1; ++u)
+        if (u < nsteps) issue(t_begin + u, u);
+    for (int u = 0; u < nsteps; ++u) {
+        const int slot = u & (STAGES - 1);
+        int younger = nsteps - 1 - u;
+        if (younger > STAGES - 2) younger = STAGES - 2;
+        wait_oldest(younger);
+        // A bare s_barrier: __syncthreads() would also fence, i.e. wait for every load still in
+        // flight to the other ring slots.  What must be complete here is only this wave's share of
+        // step u (the vmcnt wait above) and its LDS reads of step u-1 (lgkmcnt).
+        wait_lgkmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        if (u + STAGES - 1 < nsteps) issue(t_begin + u + STAGES - 1, (u + STAGES - 1) & (STAGES - 1));
+        frags(a0, b0, slot, 0);
         __builtin_amdgcn_sched_barrier(0);
-        mma(a0, b0, 0);
+        if (u > 0) mma(a1, b1, 2 * (u - 1) + 1);   // its fragments were complete before the barrier
         __builtin_amdgcn_sched_barrier(0);
-        frags(a0, b0, stage, 2);
+        frags(a1, b1, slot, 1);
         __builtin_amdgcn_sched_barrier(0);
-        mma(a1, b1, 1);
+        wait_lgkmcnt<FRAG_OPS>();                  // a0/b0 landed; a1/b1 may still be in flight
         __builtin_amdgcn_sched_barrier(0);
-        frags(a1, b1, stage, 3);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(a0, b0, 2);
-        __builtin_amdgcn_sched_barrier(0);
-        if (has_next) lstore(stage ^ 1);
-        __syncthreads();
-        if (has_next) {
-            frags(a0, b0, stage ^ 1, 0);
-            if (t + 2 < t_end) gload(t + 2);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        mma(a1, b1, 3);
+        mma(a0, b0, 2 * u);
         __builtin_amdgcn_sched_barrier(0);
     }
+    wait_lgkmcnt<0>();
+    __builtin_amdgcn_sched_barrier(0);
+    if (nsteps > 0) mma(a1, b1, 2 * (nsteps - 1) + 1);
     __syncthreads();
 
     // ------------------------------------------------------------------------------ epilogues
