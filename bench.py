@@ -52,6 +52,19 @@ def kernel_work(cfg):
 HBM_BOUND = {"compose_fwd", "compose_bwd", "mag_scale"}
 
 
+def hbm_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` as measured by the FETCH_SIZE / WRITE_SIZE counter passes whose
+    summary is kept under profiles/ (rocprofv3 cannot run inside this process); None if not recorded."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split()
+        if len(f) >= 3 and f[0] == kernel:
+            return float(f[1]) + float(f[2])
+    return None
+
+
 def cpu_baseline(cfg, inp, sample_tokens):
     """The fp64 oracle, as it stands, on the first `sample_tokens` tokens with the full weights."""
     import numpy as np
@@ -142,9 +155,37 @@ def main():
     t3 = time.perf_counter()
     ms_untraced = (t3 - t2) * 1e3 / args.steps
 
+    # what this card sustains with no other work in the way: a plain streaming copy and a
+    # register-resident MFMA loop, timed the same way (library events on the launch stream)
+    probe_bytes = 512 * 2 ** 20
+    src = torch.empty(probe_bytes, dtype=torch.uint8, device=G.DEV).fill_(1)
+    dst = torch.empty_like(src)
+    sink = torch.zeros(512, dtype=torch.float32, device=G.DEV)
+    probe_iters, probe_wgs = 512, 1024
+    for _ in range(2):
+        D.dora_probe_copy(src, dst, probe_bytes)
+        D.dora_probe_mfma(sink, probe_iters, probe_wgs)
+    torch.cuda.synchronize()
+    D.dora_trace_enable(True)
+    for _ in range(5):
+        D.dora_probe_copy(src, dst, probe_bytes)
+        D.dora_probe_mfma(sink, probe_iters, probe_wgs)
+    torch.cuda.synchronize()
+    D.dora_trace_enable(False)
+    D.dora_trace_collect()
+    copy_ms, copy_n = D.dora_trace_get(16)
+    mfma_ms, mfma_n = D.dora_trace_get(17)
+    sustained = {
+        "copy_GBps": 2.0 * probe_bytes / (copy_ms * 1e-3 / copy_n) / 1e9,
+        "mfma_bf16_TFLOPs": probe_wgs * 8 * probe_iters * 8 * 32768.0 / (mfma_ms * 1e-3 / mfma_n) / 1e12,
+        "note": "plain 16-byte-per-lane copy of 512 MiB (read + write counted) and a register-resident "
+                "v_mfma_f32_32x32x16_bf16 loop, measured in this run",
+    }
+    del src, dst
+
     work = kernel_work(cfg)
     kernels = []
-    for kid in range(D.K_COUNT):
+    for kid in range(16):
         total_ms, n = D.dora_trace_get(kid)
         if n == 0:
             continue
@@ -160,7 +201,7 @@ def main():
                         "gbytes_per_s_algorithmic": nbytes / avg_s / 1e9})
     dom = max(kernels, key=lambda k: k["avg_us"] * k["launches_per_step"])
     roofline = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
-                "unit": dom["unit"], "frac": dom["frac"], "traffic": None}
+                "unit": dom["unit"], "frac": dom["frac"], "traffic": hbm_traffic(cfg.name, dom["kernel"])}
     mfma = [k for k in kernels if k["bound"] == "mfma" and work[k["kernel"]][0] > 0]
     mfma_flops = sum(work[k["kernel"]][0] * k["launches_per_step"] for k in mfma)
     mfma_time = sum(k["avg_us"] * 1e-6 * k["launches_per_step"] for k in mfma)
@@ -177,6 +218,7 @@ def main():
         "hbm_frac_compose_fwd": next(k["frac"] for k in kernels if k["kernel"] == "compose_fwd"),
         "hbm_frac_compose_bwd": next(k["frac"] for k in kernels if k["kernel"] == "compose_bwd"),
         "ms_per_step_without_event_pairs": ms_untraced,
+        "sustained_on_this_card": sustained,
         "workspace_bytes": {"norm": D.dora_workspace_bytes(desc, D.PHASE_NORM),
                             "forward": D.dora_workspace_bytes(desc, D.PHASE_FORWARD),
                             "backward": D.dora_workspace_bytes(desc, D.PHASE_BACKWARD),

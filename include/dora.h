@@ -174,13 +174,29 @@ enum {
     DORA_K_GEMM_DX = 13,     /* dx = dz W + dh A                                       */
     DORA_K_GEMM_DA = 14,     /* dA = dh^T x                                            */
     DORA_K_GEMM_DB = 15,     /* dB = s dz^T h                                          */
-    DORA_K_COUNT = 16
+    DORA_K_PROBE_COPY = 16,  /* dora_probe_copy                                        */
+    DORA_K_PROBE_MFMA = 17,  /* dora_probe_mfma                                        */
+    DORA_K_COUNT = 18
 };
 void dora_trace_enable(int on);
 void dora_trace_reset(void);
 int dora_trace_collect(void); /* returns a dora_status */
 int dora_trace_get(int kernel_id, double* total_ms, int64_t* launches);
 const char* dora_trace_name(int kernel_id);
+
+/*
+ * Probes for measurement harnesses (not part of the method).
+ *   dora_probe_copy : dst[i] = src[i] for `bytes` bytes (device pointers, 16-byte aligned, bytes a
+ *                     multiple of 16): a plain streaming kernel that reads and writes exactly `bytes`
+ *                     each - the reference against which HBM byte counters and the achieved
+ *                     bandwidth of the compose passes can be scaled.
+ *   dora_probe_mfma : `workgroups` workgroups of 8 wavefronts each issue iters * 8
+ *                     v_mfma_f32_32x32x16_bf16 from registers (32768 flop per instruction per
+ *                     wavefront): the matrix-core rate the card sustains with no memory traffic.
+ *                     sink : device, fp32 [512], never written in practice.
+ */
+dora_status dora_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
+dora_status dora_probe_mfma(float* sink, int iters, int workgroups, void* stream);
 
 #ifdef __cplusplus
 }

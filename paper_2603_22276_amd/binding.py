@@ -16,11 +16,12 @@ LIB_PATH = os.path.join(HERE, "libdora.so")
 
 DORA_F32, DORA_BF16 = 0, 1
 PHASE_NORM, PHASE_FORWARD, PHASE_BACKWARD, PHASE_BACKWARD_RECOMPUTE, PHASE_COMPOSE_BACKWARD = range(5)
-K_COUNT = 16
+K_COUNT = 18
 
 EXPORTS = (
     "dora_workspace_bytes", "dora_norm", "dora_mag_scale", "dora_compose", "dora_compose_backward",
     "dora_project", "dora_forward", "dora_backward", "dora_status_str",
+    "dora_probe_copy", "dora_probe_mfma",
     "dora_trace_enable", "dora_trace_reset", "dora_trace_collect", "dora_trace_get", "dora_trace_name",
 )
 
@@ -59,7 +60,9 @@ def lib() -> ctypes.CDLL:
         L.dora_project.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.dora_forward.argtypes = [dp, vp, vp, vp, vp, fp, fp, vp, vp, vp, fp, vp, sz, vp]
         L.dora_backward.argtypes = [dp, vp, vp, vp, vp, vp, fp, fp, vp, vp, vp, fp, fp, fp, vp, sz, vp]
-        for f in (L.dora_norm, L.dora_mag_scale, L.dora_compose, L.dora_compose_backward, L.dora_project, L.dora_forward,
+        L.dora_probe_copy.argtypes = [vp, vp, sz, vp]
+        L.dora_probe_mfma.argtypes = [fp, ctypes.c_int, ctypes.c_int, vp]
+        for f in (L.dora_probe_copy, L.dora_probe_mfma, L.dora_norm, L.dora_mag_scale, L.dora_compose, L.dora_compose_backward, L.dora_project, L.dora_forward,
                   L.dora_backward, L.dora_trace_collect, L.dora_trace_get):
             f.restype = ctypes.c_int
         L.dora_status_str.argtypes = [ctypes.c_int]
@@ -152,6 +155,14 @@ def dora_backward(desc, dy, x, W, A, B, m, w_norm, saved_h, saved_inner, dx, dA,
     _check(lib().dora_backward(ctypes.byref(desc), _p(dy), _p(x), _p(W), _p(A), _p(B), _p(m), _p(w_norm), _p(saved_h),
                                _p(saved_inner), _p(dx), _p(dA), _p(dB), _p(dm), _p(ws), _nbytes(ws), _stream(stream)),
            "dora_backward")
+
+
+def dora_probe_copy(src, dst, nbytes: int, stream=None) -> None:
+    _check(lib().dora_probe_copy(_p(src), _p(dst), int(nbytes), _stream(stream)), "dora_probe_copy")
+
+
+def dora_probe_mfma(sink, iters: int, workgroups: int, stream=None) -> None:
+    _check(lib().dora_probe_mfma(_p(sink), int(iters), int(workgroups), _stream(stream)), "dora_probe_mfma")
 
 
 def dora_trace_enable(on: bool) -> None:

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdora.so")
-SOURCES = ["dora_api.hip", "gemm_bf16.hip", "elementwise.hip", "sgemm_f32.hip"]
+SOURCES = ["dora_api.hip", "gemm_bf16.hip", "elementwise.hip", "sgemm_f32.hip", "probes.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

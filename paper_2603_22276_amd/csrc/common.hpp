@@ -26,9 +26,13 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
     uint32_t r = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
     return (f != f) ? 0x7fc0u : r;
 }
+// two fp32 -> packed bf16 pair with the hardware converter (v_cvt_pk_bf16_f32: nearest-even)
+typedef __bf16 bf16x2_hw_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_hw_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 {
-    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+    f32x2_hw_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_hw_t));
 }
 
 // ---- kernel timing hook (see dora_trace_* in dora.h) ------------------------------------------
@@ -69,6 +73,7 @@ struct GemmArgs {
     void* c;
     int64_t ldc;
     int ksplit;                // split of segment 0's K range (nseg must be 1 when > 1)
+    int tag;                   // 0 or 1: selects a differently named (otherwise identical) kernel instance
     // EPI_ROWDOT only
     const bf16_t* rowdot;      // R [M, ld_rowdot] bf16
     int64_t ld_rowdot;
@@ -101,7 +106,7 @@ hipError_t launch_sgemm_f32(const SgemmArgs& a, int trace_id, hipStream_t stream
 hipError_t launch_mag_scale(const float* m, const float* c, float eps, float* g, float* gm1, int d_out, hipStream_t st);
 hipError_t launch_compose_fwd(int dtype, const void* base, const void* lora, const float* g, const float* gm1, float s,
                               void* out, int write_delta, void* inner, int64_t tokens, int d_out, hipStream_t st);
-int compose_bwd_slabs(int64_t tokens);
+int compose_bwd_slabs(int64_t tokens, int d_out, int dtype);
 hipError_t launch_compose_bwd(int dtype, const void* dy, const void* inner, const float* g, void* dz,
                               float* partial /* [slabs][d_out] or nullptr */, int64_t tokens, int d_out, hipStream_t st);
 hipError_t launch_dm_final(const float* partial, int slabs, const float* c, float eps, float* dm, int d_out, hipStream_t st);
@@ -112,5 +117,8 @@ hipError_t launch_rownorm_s0_bf16(const bf16_t* W, float* c, int d_out, int d_in
 // fp32 path: base_sq, cross, ba_sq and Eq. 5 from W, B, U = W A^T, BG = B G (all fp32)
 hipError_t launch_rownorm_f32(const float* W, const float* B, const float* U, const float* BG, double s, float* c,
                               int d_out, int d_in, int r, hipStream_t st);
+
+hipError_t launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t st);
+hipError_t launch_mfma_probe(float* sink, int iters, int workgroups, hipStream_t st);
 
 }  // namespace dora

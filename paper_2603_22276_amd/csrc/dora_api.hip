@@ -171,6 +171,7 @@ hipError_t contract(int dtype, bool a_kc, bool b_kc, int M, int N, const Seg* se
         g.nseg = nseg; g.M = M; g.N = N; g.a_kcontig = a_kc; g.b_kcontig = b_kc;
         g.epilogue = c_f32 ? EPI_STORE_F32 : EPI_STORE_BF16;
         g.alpha = alpha; g.c = c; g.ldc = ldc; g.ksplit = 1;
+        g.tag = (trace_id == DORA_K_GEMM_LORA || trace_id == DORA_K_GEMM_DB) ? 1 : 0;
         return launch_gemm_bf16(g, trace_id, st);
     }
     SgemmArgs g;
@@ -218,7 +219,7 @@ dora_status norm_impl(const dora_desc* d, const void* W, const void* A, const vo
         g.seg[0] = GemmSeg{(const bf16_t*)B, n.Ghi, r, r, r};
         g.seg[1] = GemmSeg{(const bf16_t*)B, n.Glo, r, r, r};
         g.nseg = 2; g.M = d_out; g.N = r; g.a_kcontig = 1; g.b_kcontig = 1; g.epilogue = EPI_ROWDOT; g.alpha = 1.f;
-        g.ksplit = 1; g.rowdot = (const bf16_t*)B; g.ld_rowdot = r; g.rowdot_partial = n.ba_p;
+        g.ksplit = 1; g.rowdot = (const bf16_t*)B; g.ld_rowdot = r; g.rowdot_partial = n.ba_p; g.tag = 1;
         DORA_HIP(launch_gemm_bf16(g, DORA_K_BA_SQ, st));
         DORA_HIP(launch_norm_final(n.base_p, n.ks_u, n.cross_p, n.ks_u * n.tiles_n, n.ba_p, n.tiles_n, (double)d->s, c,
                                    d_out, st));
@@ -265,7 +266,7 @@ void plan_bwd(const dora_desc* d, Bump& b, BwdPlan& p, bool need_norm, bool need
     p.c = b.take<float>((size_t)d->d_out);
     p.g = b.take<float>((size_t)d->d_out);
     p.gm1 = b.take<float>((size_t)d->d_out);
-    p.dm_partial = b.take<float>((size_t)compose_bwd_slabs(d->tokens) * d->d_out);
+    p.dm_partial = b.take<float>((size_t)compose_bwd_slabs(d->tokens, (int)d->d_out, d->dtype) * d->d_out);
     p.dz = b.take_bytes((size_t)d->tokens * d->d_out * esize(d->dtype));
     p.dh = b.take_bytes((size_t)d->tokens * d->r * esize(d->dtype));
     if (need_h) p.h = b.take_bytes((size_t)d->tokens * d->r * esize(d->dtype));
@@ -321,7 +322,7 @@ size_t dora_workspace_bytes(const dora_desc* desc, int phase)
 {
     if (phase == DORA_PHASE_COMPOSE_BACKWARD) {
         if (check_desc(desc, false) != DORA_OK) return 0;
-        return up256((size_t)compose_bwd_slabs(desc->tokens) * desc->d_out * sizeof(float));
+        return up256((size_t)compose_bwd_slabs(desc->tokens, (int)desc->d_out, desc->dtype) * desc->d_out * sizeof(float));
     }
     if (check_desc(desc, true) != DORA_OK) return 0;
     Bump b(nullptr);
@@ -391,7 +392,7 @@ dora_status dora_compose_backward(const dora_desc* desc, const void* dy, const v
     hipStream_t s = (hipStream_t)stream;
     DORA_HIP(launch_compose_bwd(desc->dtype, dy, inner, g, dz, partial, desc->tokens, (int)desc->d_out, s));
     if (dm)
-        DORA_HIP(launch_dm_final(partial, compose_bwd_slabs(desc->tokens), w_norm, eff_eps(desc), dm, (int)desc->d_out, s));
+        DORA_HIP(launch_dm_final(partial, compose_bwd_slabs(desc->tokens, (int)desc->d_out, desc->dtype), w_norm, eff_eps(desc), dm, (int)desc->d_out, s));
     return DORA_OK;
 }
 
@@ -499,7 +500,7 @@ dora_status dora_backward(const dora_desc* desc, const void* dy, const void* x, 
 
     // compose backward: dz = g*dy and the fused two-stage column reduction for dm
     DORA_HIP(launch_compose_bwd(dt, dy, inner, p.g, p.dz, dm ? p.dm_partial : nullptr, T, d_out, s));
-    if (dm) DORA_HIP(launch_dm_final(p.dm_partial, compose_bwd_slabs(T), c, eff_eps(desc), dm, d_out, s));
+    if (dm) DORA_HIP(launch_dm_final(p.dm_partial, compose_bwd_slabs(T, d_out, dt), c, eff_eps(desc), dm, d_out, s));
 
     // dh = s * dz B   (gradient reaching h = x A^T)
     if (dx || dA) {
@@ -518,6 +519,22 @@ dora_status dora_backward(const dora_desc* desc, const void* dy, const void* x, 
         Seg sb{p.dz, d_out, h, r, T};
         DORA_HIP(contract(dt, false, false, d_out, r, &sb, 1, desc->s, dB, r, true, DORA_K_GEMM_DB, s));
     }
+    return DORA_OK;
+}
+
+dora_status dora_probe_copy(const void* src, void* dst, size_t bytes, void* stream)
+{
+    DORA_REQ_PTR(src); DORA_REQ_PTR(dst);
+    if (bytes % 16) return DORA_ERR_SHAPE;
+    DORA_HIP(launch_copy_probe(src, dst, bytes, (hipStream_t)stream));
+    return DORA_OK;
+}
+
+dora_status dora_probe_mfma(float* sink, int iters, int workgroups, void* stream)
+{
+    DORA_REQ_PTR(sink);
+    if (iters < 0 || workgroups < 0 || workgroups > 65536) return DORA_ERR_SHAPE;
+    DORA_HIP(launch_mfma_probe(sink, iters, workgroups, (hipStream_t)stream));
     return DORA_OK;
 }
 
@@ -558,7 +575,7 @@ const char* dora_trace_name(int kernel_id)
     static const char* names[DORA_K_COUNT] = {
         "norm_cross_WAt", "gram_AAt", "gram_reduce", "ba_sq_BGB", "norm_final", "mag_scale", "gemm_base_xWt",
         "gemm_h_xAt", "gemm_lora_hBt", "compose_fwd", "compose_bwd", "dm_final", "gemm_dh_dzB", "gemm_dx",
-        "gemm_dA", "gemm_dB"};
+        "gemm_dA", "gemm_dB", "probe_copy", "probe_mfma"};
     return (kernel_id >= 0 && kernel_id < DORA_K_COUNT) ? names[kernel_id] : "?";
 }
 

@@ -1,0 +1,69 @@
+// Measurement probes (not part of the method): a plain streaming copy and a register-resident MFMA
+// loop, so that a harness can state what this particular card sustains next to the datasheet peaks
+// and can calibrate the HBM byte counters against a kernel whose traffic is known exactly.
+#include "common.hpp"
+
+namespace dora {
+namespace {
+
+typedef unsigned int u32x4_nt_t __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void copy_probe_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16)
+{
+    // four 16-byte vectors in flight per lane, non-temporal stores (the form that streams fastest here)
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += 4 * stride) {
+        uint4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (i + u * stride < n16) v[u] = src[i + u * stride];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (i + u * stride < n16)
+                __builtin_nontemporal_store(__builtin_bit_cast(u32x4_nt_t, v[u]), reinterpret_cast<u32x4_nt_t*>(dst + i + u * stride));
+    }
+}
+
+// 8 independent accumulator tiles per wave, operands never leave registers
+__global__ __launch_bounds__(512) void mfma_probe_kernel(float* sink, int iters)
+{
+    bf16x8_t a, b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { a[e] = (__bf16)(0.001f * (float)((threadIdx.x + e) & 15)); b[e] = (__bf16)(0.002f * (float)((threadIdx.x * 3 + e) & 15)); }
+    f32x16_t acc[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[t], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) s += acc[t][0] + acc[t][15];
+    if (s == 12345.678f) sink[threadIdx.x] = s;  // keeps the loop alive; never true in practice
+}
+
+}  // namespace
+
+hipError_t launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t st)
+{
+    size_t n16 = bytes / 16;
+    if (n16 == 0) return hipSuccess;
+    TraceScope ts(DORA_K_PROBE_COPY, st);
+    size_t wgs = (n16 + 1023) / 1024;
+    if (wgs > 8192) wgs = 8192;
+    copy_probe_kernel<<<dim3((unsigned)wgs), dim3(256), 0, st>>>((const uint4*)src, (uint4*)dst, n16);
+    return hipGetLastError();
+}
+
+hipError_t launch_mfma_probe(float* sink, int iters, int workgroups, hipStream_t st)
+{
+    if (iters <= 0 || workgroups <= 0) return hipSuccess;
+    TraceScope ts(DORA_K_PROBE_MFMA, st);
+    mfma_probe_kernel<<<dim3(workgroups), dim3(512), 0, st>>>(sink, iters);
+    return hipGetLastError();
+}
+
+}  // namespace dora

@@ -285,3 +285,15 @@ def test_zero_tokens(dtype):
     G.assert_norm_close(G.to_f64(out["c"]), ref, G.TOL[dtype]["norm"])
     g = mod.backward()
     assert float(g["dA"].abs().max()) == 0.0 and float(g["dB"].abs().max()) == 0.0 and float(g["dm"].abs().max()) == 0.0
+
+
+def test_probes_run_and_copy_is_exact():
+    n = 3 * 2 ** 20 + 4096 + 16
+    src = torch.randint(0, 255, (n,), dtype=torch.uint8, device=G.DEV)
+    dst = torch.zeros_like(src)
+    D.dora_probe_copy(src, dst, n)
+    assert torch.equal(src, dst)
+    sink = torch.zeros(512, dtype=torch.float32, device=G.DEV)
+    D.dora_probe_mfma(sink, 4, 8)
+    torch.cuda.synchronize()
+    assert float(sink.abs().max()) == 0.0
