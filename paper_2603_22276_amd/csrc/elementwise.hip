@@ -299,7 +299,6 @@ __global__ __launch_bounds__(DMF_W* DMF_H) void dm_final_kernel(const float* __r
     }
 }
 
-constexpr int FWD_ROWS_PER_WG = 16;   // one batch of CH * UNROLL rows: no loop, many short workgroups
 
 }  // namespace
 
@@ -349,12 +348,25 @@ hipError_t launch_rownorm_f32(const float* W, const float* B, const float* U, co
     return hipGetLastError();
 }
 
+// Rows per workgroup.  Measured inside the whole forward + backward sequence (where these passes
+// start at the clock the preceding contraction left behind) long slabs win: 128 rows forward, 64
+// backward; shorter ones are chosen only when the launch would otherwise leave CUs without work.
+static int slab_rows(int preferred, int64_t tokens, int d_out, int dtype)
+{
+    const int n = dtype == DORA_BF16 ? 8 : 4;
+    const int64_t col_blocks = (d_out / n + CW - 1) / CW;
+    for (int rows = preferred; rows > 16; rows >>= 1)
+        if (col_blocks * ((tokens + rows - 1) / rows) >= 512) return rows;
+    return 16;
+}
+
 template <typename T>
 static hipError_t compose_fwd_t(const void* base, const void* lora, const float* g, const float* gm1, float s, void* out,
                                 int write_delta, void* inner, int64_t tokens, int d_out, hipStream_t st)
 {
     constexpr int N = Vec<T>::N;
     int cpr = d_out / N;
+    const int FWD_ROWS_PER_WG = slab_rows(128, tokens, d_out, sizeof(T) == 2 ? DORA_BF16 : DORA_F32);
     dim3 grid((cpr + CW - 1) / CW, (unsigned)((tokens + FWD_ROWS_PER_WG - 1) / FWD_ROWS_PER_WG));
     dim3 block(CW, CH);
     const T* b = (const T*)base;
@@ -379,16 +391,7 @@ hipError_t launch_compose_fwd(int dtype, const void* base, const void* lora, con
     return compose_fwd_t<float>(base, lora, g, gm1, s, out, write_delta, inner, tokens, d_out, st);
 }
 
-// Rows per workgroup of the backward pass: long slabs keep the dm partials small and stream best;
-// shorter ones are chosen only when the launch would otherwise leave CUs without work.
-static int compose_bwd_rows(int64_t tokens, int d_out, int dtype)
-{
-    const int n = dtype == DORA_BF16 ? 8 : 4;
-    const int64_t col_blocks = (d_out / n + CW - 1) / CW;
-    for (int rows = 256; rows > 16; rows >>= 1)
-        if (col_blocks * ((tokens + rows - 1) / rows) >= 512) return rows;
-    return 16;
-}
+static int compose_bwd_rows(int64_t tokens, int d_out, int dtype) { return slab_rows(64, tokens, d_out, dtype); }
 
 int compose_bwd_slabs(int64_t tokens, int d_out, int dtype)
 {
