@@ -52,8 +52,8 @@ hipError_t launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream
     size_t n16 = bytes / 16;
     if (n16 == 0) return hipSuccess;
     TraceScope ts(DORA_K_PROBE_COPY, st);
-    size_t wgs = (n16 + 1023) / 1024;
-    if (wgs > 8192) wgs = 8192;
+    size_t wgs = (n16 + 1023) / 1024;  // one batch of four vectors per lane, no loop
+    if (wgs > 0x7fffffffu) return hipErrorInvalidValue;
     copy_probe_kernel<<<dim3((unsigned)wgs), dim3(256), 0, st>>>((const uint4*)src, (uint4*)dst, n16);
     return hipGetLastError();
 }
