@@ -122,7 +122,10 @@ struct OperandLoader {
             row = ((pos % (ROWS / 8)) ^ ((k & 3) << 2)) * 8;
         }
     }
-    static __device__ __forceinline__ void offsets(uint32_t (&vo)[NL], int64_t ld, int row0, int rows, int wave, int lane)
+    // per-lane constants of load i: byte offset of its chunk at k0 = 0 (0xFFFFFFFF if its row is out of
+    // range) and the chunk's k index inside the K step
+    static __device__ __forceinline__ void offsets(uint32_t (&vo)[NL], int (&kl)[NL], int64_t ld, int row0, int rows,
+                                                   int wave, int lane)
     {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
@@ -131,22 +134,19 @@ struct OperandLoader {
             int grow = row0 + row;
             uint32_t off = KCONTIG ? (uint32_t)(((int64_t)grow * ld + k) * 2) : (uint32_t)(((int64_t)k * ld + grow) * 2);
             vo[i] = (grow < rows) ? off : 0xFFFFFFFFu;
+            kl[i] = k;
         }
     }
-    template <bool TAIL>
+    // Branch-free issue of one K step: chunks whose k index is at or beyond `krem` (the k left in the
+    // segment; <= 0 once the schedule is exhausted) are pushed out of range and load zeros.
     static __device__ __forceinline__ void issue(char* tile, __amdgpu_buffer_rsrc_t rs, const uint32_t (&vo)[NL],
-                                                 int64_t ld, int k0, int K, int wave, int lane)
+                                                 const int (&kl)[NL], uint32_t soffset, int krem, int wave)
     {
-        const uint32_t so = KCONTIG ? (uint32_t)(k0 * 2) : (uint32_t)((int64_t)k0 * ld * 2);
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
-            uint32_t off = vo[i];
-            if (TAIL) {
-                int row, k;
-                chunk_of(i, wave, lane, row, k);
-                if (k0 + k >= K) off = 0xFFFFFFFFu;
-            }
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_ptr_t)(tile + (i * WAVES + wave) * 1024), 16, off, so, 0, 0);
+            const uint32_t off = (kl[i] < krem) ? vo[i] : 0xFFFFFFFFu;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_ptr_t)(tile + (i * WAVES + wave) * 1024), 16, off,
+                                                     soffset, 0, 0);
         }
     }
 };
@@ -238,33 +238,43 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmArgs p)
 
     typedef OperandLoader<BM, T::NLA, T::WAVES, A_KC> LA;
     typedef OperandLoader<BN, T::NLB, T::WAVES, B_KC> LB;
-    uint32_t voa[T::NLA], vob[T::NLB];   // per-lane byte offsets into the current segment's operands
-    __amdgpu_buffer_rsrc_t rsa, rsb;     // buffer descriptors of the current segment's operands
-    int64_t lda_cur = 0, ldb_cur = 0;
-    int K_cur = 0;
-    int seg_loaded = -1;
-
-    // issue the global -> LDS loads of K step t (absolute index) into ring slot `slot`
-    auto issue = [&](int t, int slot) {
-        const int s = (t >= kt0_total) ? 1 : 0;
-        if (s != seg_loaded) {
-            const GemmSeg& sg = p.seg[s];
-            lda_cur = sg.lda; ldb_cur = sg.ldb; K_cur = sg.K;
-            rsa = LA::make_rsrc(sg.a, sg.lda, p.M, sg.K);
-            rsb = LB::make_rsrc(sg.b, sg.ldb, p.N, sg.K);
-            LA::offsets(voa, sg.lda, m0, p.M, wave, lane);
-            LB::offsets(vob, sg.ldb, n0, p.N, wave, lane);
-            seg_loaded = s;
-        }
-        const int k0 = (s ? t - kt0_total : t) * BK;
+    // Issue cursor: descriptors, per-lane offsets and the running scalar offsets of the segment the
+    // global -> LDS loads are currently walking.  It runs STAGES-1 steps ahead of the MFMAs and moves
+    // to the next segment (or to "exhausted": every further step loads zeros) on its own.
+    uint32_t voa[T::NLA], vob[T::NLB];
+    int kla[T::NLA], klb[T::NLB];
+    __amdgpu_buffer_rsrc_t rsa, rsb;
+    uint32_t so_a = 0, so_b = 0, so_step_a = 0, so_step_b = 0;  // scalar byte offsets and their per-step increments
+    int krem = 0;        // k still to load in the cursor's segment (<= 0: exhausted)
+    int seg_cur = 0;
+    auto open_segment = [&](int sidx, int k_first, int k_last) {
+        const GemmSeg& sg = p.seg[sidx];
+        rsa = LA::make_rsrc(sg.a, sg.lda, p.M, sg.K);
+        rsb = LB::make_rsrc(sg.b, sg.ldb, p.N, sg.K);
+        LA::offsets(voa, kla, sg.lda, m0, p.M, wave, lane);
+        LB::offsets(vob, klb, sg.ldb, n0, p.N, wave, lane);
+        so_step_a = A_KC ? (uint32_t)(BK * 2) : (uint32_t)(BK * sg.lda * 2);
+        so_step_b = B_KC ? (uint32_t)(BK * 2) : (uint32_t)(BK * sg.ldb * 2);
+        so_a = A_KC ? (uint32_t)(k_first * 2) : (uint32_t)((int64_t)k_first * sg.lda * 2);
+        so_b = B_KC ? (uint32_t)(k_first * 2) : (uint32_t)((int64_t)k_first * sg.ldb * 2);
+        krem = (k_last < sg.K ? k_last : sg.K) - k_first;
+        seg_cur = sidx;
+    };
+    // segment 0 covers K steps [t_begin, min(t_end, kt0_total)); segment 1 (never split) the rest
+    const bool has_seg1 = (p.nseg > 1) && (t_end > kt0_total);
+    {
+        const int e0 = t_end < kt0_total ? t_end : kt0_total;
+        open_segment(0, t_begin * BK, e0 * BK);
+        if (krem <= 0 && has_seg1) open_segment(1, 0, p.seg[1].K);
+    }
+    auto issue = [&](int slot) {
         char* st = smem + slot * T::STAGE_BYTES;
-        if (k0 + BK <= K_cur) {
-            LA::template issue<false>(st, rsa, voa, lda_cur, k0, K_cur, wave, lane);
-            LB::template issue<false>(st + T::A_BYTES, rsb, vob, ldb_cur, k0, K_cur, wave, lane);
-        } else {
-            LA::template issue<true>(st, rsa, voa, lda_cur, k0, K_cur, wave, lane);
-            LB::template issue<true>(st + T::A_BYTES, rsb, vob, ldb_cur, k0, K_cur, wave, lane);
-        }
+        LA::issue(st, rsa, voa, kla, so_a, krem, wave);
+        LB::issue(st + T::A_BYTES, rsb, vob, klb, so_b, krem, wave);
+    };
+    auto advance = [&]() {
+        so_a += so_step_a; so_b += so_step_b; krem -= BK;
+        if (krem <= 0 && seg_cur == 0 && has_seg1) open_segment(1, 0, p.seg[1].K);
     };
     auto frags = [&](bf16x8_t (&af)[MT], bf16x8_t (&bfr)[NT], int slot, int kk) {
         const char* sa = smem + slot * T::STAGE_BYTES;
@@ -298,36 +308,27 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmArgs p)
             }
         }
     };
-    // wait until the loads of the oldest outstanding K step have landed, given how many younger
-    // steps are in flight behind it
-    auto wait_oldest = [&](int younger) {
-        if (younger >= 2) wait_vmcnt<2 * LPT>();
-        else if (younger == 1) wait_vmcnt<LPT>();
-        else wait_vmcnt<0>();
-    };
-
-    // Pipeline.  Ring slot u % 4 holds K step u.  Up to three steps are in flight behind the one
-    // being multiplied.  Per step: wait for its data, workgroup barrier (which also says every wave
-    // is done reading step u-1), refill the slot step u-1 occupied with step u+3, read the first
-    // fragments of step u, and only then run the last MFMAs of step u-1 - they cover the latency
-    // of those fragment reads.
+    // Pipeline.  Ring slot u % 4 holds K step u; three steps are always in flight behind the one
+    // being multiplied (past the end of the schedule they are loads of zeros into free slots, which
+    // keeps the vmcnt bookkeeping uniform).  Per step: wait for its data, workgroup barrier (which
+    // also says every wave is done reading step u-1), read the first fragments of step u, then run
+    // the last MFMAs of step u-1 with the loads of step u+3 issued in their shadow.
     bf16x8_t a0[MT], b0[NT], a1[MT], b1[NT];
+    if (nsteps > 0) {
 #pragma unroll
-    for (int u = 0; u < STAGES - 1; ++u)
-        if (u < nsteps) issue(t_begin + u, u);
+        for (int u = 0; u < STAGES - 1; ++u) { issue(u); advance(); }
+    }
     for (int u = 0; u < nsteps; ++u) {
         const int slot = u & (STAGES - 1);
-        int younger = nsteps - 1 - u;
-        if (younger > STAGES - 2) younger = STAGES - 2;
-        wait_oldest(younger);
+        wait_vmcnt<2 * LPT>();
         // A bare s_barrier: __syncthreads() would also fence, i.e. wait for every load still in
         // flight to the other ring slots.  What must be complete here is only this wave's share of
         // step u (the vmcnt wait above) and its LDS reads of step u-1 (lgkmcnt).
         wait_lgkmcnt<0>();
         __builtin_amdgcn_s_barrier();
-        if (u + STAGES - 1 < nsteps) issue(t_begin + u + STAGES - 1, (u + STAGES - 1) & (STAGES - 1));
         frags(a0, b0, slot, 0);
         __builtin_amdgcn_sched_barrier(0);
+        issue((u + STAGES - 1) & (STAGES - 1));
         if (u > 0) mma(a1, b1, 2 * (u - 1) + 1);   // its fragments were complete before the barrier
         __builtin_amdgcn_sched_barrier(0);
         frags(a1, b1, slot, 1);
@@ -336,7 +337,9 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmArgs p)
         __builtin_amdgcn_sched_barrier(0);
         mma(a0, b0, 2 * u);
         __builtin_amdgcn_sched_barrier(0);
+        advance();
     }
+    wait_vmcnt<0>();
     wait_lgkmcnt<0>();
     __builtin_amdgcn_sched_barrier(0);
     if (nsteps > 0) mma(a1, b1, 2 * (nsteps - 1) + 1);
