@@ -172,7 +172,7 @@ enum {
     DORA_K_DM_FINAL = 11,    /* second stage of the dm column reduction                */
     DORA_K_GEMM_DH = 12,     /* dh = s dz B                                            */
     DORA_K_GEMM_DX = 13,     /* dx = dz W + dh A                                       */
-    DORA_K_GEMM_DA = 14,     /* dA = dh^T x                                            */
+    DORA_K_GEMM_DA = 14,     /* dA = dh^T x (bf16: the same launch also computes dB)   */
     DORA_K_GEMM_DB = 15,     /* dB = s dz^T h                                          */
     DORA_K_PROBE_COPY = 16,  /* dora_probe_copy                                        */
     DORA_K_PROBE_MFMA = 17,  /* dora_probe_mfma                                        */

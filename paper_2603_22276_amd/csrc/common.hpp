@@ -81,9 +81,16 @@ struct GemmArgs {
     float* base_sq_partial;    // [ksplit][M] or nullptr
 };
 
+struct GemmPair {
+    GemmArgs g[2];
+    int count0;  // workgroups of g[0]; the rest of the grid belongs to g[1]
+};
+
 // number of N tiles the ROWDOT epilogue will produce partials for (depends on the tile chosen)
 int gemm_bf16_tiles_n(const GemmArgs& a);
 hipError_t launch_gemm_bf16(const GemmArgs& a, int trace_id, hipStream_t stream);
+// two independent problems of the same kind (layouts, epilogue) in one launch
+hipError_t launch_gemm_bf16_pair(const GemmArgs& a, const GemmArgs& b, int trace_id, hipStream_t stream);
 
 // ---- fp32 GEMM (simple LDS-tiled VALU kernel; the fp32 configuration is small) ------------------
 struct SgemmSeg {

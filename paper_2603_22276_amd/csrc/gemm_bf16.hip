@@ -194,8 +194,13 @@ __device__ __forceinline__ void wait_lgkmcnt()
 // TAG takes no part in the computation: it gives the two contractions that would otherwise share an
 // instantiation separate kernel names, so that a profiler's per-kernel statistics line up with them.
 template <class T, bool A_KC, bool B_KC, int EPI, int TAG>
-__global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmArgs p)
+__global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
 {
+    // one launch may carry two independent problems of the same kind (e.g. base = x W^T and
+    // h = x A^T, or dA and dB): workgroups past count0 belong to the second one
+    const bool second = (int)blockIdx.x >= grp.count0;
+    const GemmArgs& p = second ? grp.g[1] : grp.g[0];
+    const int wg_id = (int)blockIdx.x - (second ? grp.count0 : 0);
     constexpr int BM = T::BM, BN = T::BN, MT = T::MT, NT = T::NT;
     constexpr int FRAG_OPS = MT * (A_KC ? 1 : 2) + NT * (B_KC ? 1 : 2);  // LDS reads per k-step of 16
     constexpr int LPT = T::NLA + T::NLB;  // load instructions per K step per lane
@@ -209,7 +214,7 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmArgs p)
     const int wm0 = wm * T::WM, wn0 = wn * T::WN;
 
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
-    const TileCoord tc = map_tile(blockIdx.x, tiles_m, tiles_n, p.ksplit);
+    const TileCoord tc = map_tile(wg_id, tiles_m, tiles_n, p.ksplit);
     const int m0 = tc.tm * BM, n0 = tc.tn * BN;
 
     // flattened K-step schedule over the segments; split-K slices segment 0 only
@@ -427,16 +432,26 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmArgs p)
     }
 }
 
-template <class T, bool A_KC, bool B_KC, int EPI>
-hipError_t launch_one(const GemmArgs& a, hipStream_t stream)
+template <class T>
+int grid_of(const GemmArgs& a)
 {
-    int tiles_m = (a.M + T::BM - 1) / T::BM, tiles_n = (a.N + T::BN - 1) / T::BN;
-    int grid = tiles_m * tiles_n * a.ksplit;
+    if (a.M <= 0 || a.N <= 0) return 0;
+    return ((a.M + T::BM - 1) / T::BM) * ((a.N + T::BN - 1) / T::BN) * a.ksplit;
+}
+
+template <class T, bool A_KC, bool B_KC, int EPI>
+hipError_t launch_one(const GemmArgs& a, const GemmArgs* b, hipStream_t stream)
+{
+    GemmPair grp;
+    grp.g[0] = a;
+    grp.g[1] = b ? *b : a;
+    grp.count0 = grid_of<T>(a);
+    const int grid = grp.count0 + (b ? grid_of<T>(*b) : 0);
     if (grid == 0) return hipSuccess;
     if (a.tag)
-        gemm_bf16_kernel<T, A_KC, B_KC, EPI, 1><<<dim3(grid), dim3(T::THREADS), 0, stream>>>(a);
+        gemm_bf16_kernel<T, A_KC, B_KC, EPI, 1><<<dim3(grid), dim3(T::THREADS), 0, stream>>>(grp);
     else
-        gemm_bf16_kernel<T, A_KC, B_KC, EPI, 0><<<dim3(grid), dim3(T::THREADS), 0, stream>>>(a);
+        gemm_bf16_kernel<T, A_KC, B_KC, EPI, 0><<<dim3(grid), dim3(T::THREADS), 0, stream>>>(grp);
     return hipGetLastError();
 }
 
@@ -447,6 +462,25 @@ bool use_big(const GemmArgs& a)
     return a.epilogue == EPI_STORE_BF16 && a.ksplit == 1 && big_tiles >= 256;
 }
 
+hipError_t dispatch(const GemmArgs& a, const GemmArgs* b, hipStream_t stream)
+{
+    const bool big = use_big(a);
+#define DORA_GEMM_CASE(AKC, BKC, E)                                                     \
+    if (a.a_kcontig == (AKC) && a.b_kcontig == (BKC) && a.epilogue == (E))              \
+        return big ? launch_one<TileBig, AKC, BKC, E>(a, b, stream) : launch_one<TileMed, AKC, BKC, E>(a, b, stream);
+    DORA_GEMM_CASE(true, true, EPI_STORE_BF16)
+    DORA_GEMM_CASE(true, false, EPI_STORE_BF16)
+#undef DORA_GEMM_CASE
+#define DORA_GEMM_CASE_MED(AKC, BKC, E)                                                 \
+    if (a.a_kcontig == (AKC) && a.b_kcontig == (BKC) && a.epilogue == (E))              \
+        return launch_one<TileMed, AKC, BKC, E>(a, b, stream);
+    DORA_GEMM_CASE_MED(true, true, EPI_STORE_F32)
+    DORA_GEMM_CASE_MED(true, true, EPI_ROWDOT)
+    DORA_GEMM_CASE_MED(false, false, EPI_STORE_F32)
+#undef DORA_GEMM_CASE_MED
+    return hipErrorInvalidValue;
+}
+
 }  // namespace
 
 int gemm_bf16_tiles_n(const GemmArgs& a) { return (a.N + TileMed::BN - 1) / TileMed::BN; }
@@ -455,21 +489,18 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, int trace_id, hipStream_t stream)
 {
     if (a.M == 0 || a.N == 0) return hipSuccess;
     TraceScope ts(trace_id, stream);
-    const bool big = use_big(a);
-#define DORA_GEMM_CASE(AKC, BKC, E)                                                     \
-    if (a.a_kcontig == (AKC) && a.b_kcontig == (BKC) && a.epilogue == (E))              \
-        return big ? launch_one<TileBig, AKC, BKC, E>(a, stream) : launch_one<TileMed, AKC, BKC, E>(a, stream);
-    DORA_GEMM_CASE(true, true, EPI_STORE_BF16)
-    DORA_GEMM_CASE(true, false, EPI_STORE_BF16)
-#undef DORA_GEMM_CASE
-#define DORA_GEMM_CASE_MED(AKC, BKC, E)                                                 \
-    if (a.a_kcontig == (AKC) && a.b_kcontig == (BKC) && a.epilogue == (E))              \
-        return launch_one<TileMed, AKC, BKC, E>(a, stream);
-    DORA_GEMM_CASE_MED(true, true, EPI_STORE_F32)
-    DORA_GEMM_CASE_MED(true, true, EPI_ROWDOT)
-    DORA_GEMM_CASE_MED(false, false, EPI_STORE_F32)
-#undef DORA_GEMM_CASE_MED
-    return hipErrorInvalidValue;
+    return dispatch(a, nullptr, stream);
+}
+
+hipError_t launch_gemm_bf16_pair(const GemmArgs& a, const GemmArgs& b, int trace_id, hipStream_t stream)
+{
+    // both problems run the same kernel instance: same operand layouts, epilogue, no split-K
+    if (a.a_kcontig != b.a_kcontig || a.b_kcontig != b.b_kcontig || a.epilogue != b.epilogue || a.ksplit != 1 ||
+        b.ksplit != 1)
+        return hipErrorInvalidValue;
+    if ((a.M == 0 || a.N == 0) && (b.M == 0 || b.N == 0)) return hipSuccess;
+    TraceScope ts(trace_id, stream);
+    return dispatch(a, &b, stream);
 }
 
 }  // namespace dora
