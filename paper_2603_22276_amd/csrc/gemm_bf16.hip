@@ -323,6 +323,56 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
 #pragma unroll
         for (int u = 0; u < STAGES - 1; ++u) { issue(u); advance(); }
     }
+    if (T::WAVES == 8) {
+        // Ping-pong (8 waves = two per SIMD).  The waves form two groups of four, one wave of each
+        // group on every SIMD.  Time is cut into phases separated by workgroup barriers; in each phase
+        // one group runs the 16 MFMAs of a K step from registers while the other reads the fragments
+        // of its next step from LDS and issues its share of the global loads, then the roles swap:
+        //     phase 2u   : group 0 multiplies step u   | group 1 fetches step u
+        //     phase 2u+1 : group 0 fetches step u+1    | group 1 multiplies step u
+        // so the matrix pipe of every SIMD always has one wave feeding it and the memory
+        // instructions of the other wave issue in its shadow.
+        const int grp_id = wave >> 2;
+        auto fetch = [&](int u) {   // fragments of step u -> registers; refill the slot step u-1 used
+            const int slot = u & (STAGES - 1);
+            frags(a0, b0, slot, 0);
+            frags(a1, b1, slot, 1);
+            issue((u + STAGES - 1) & (STAGES - 1));
+            advance();
+        };
+        auto compute = [&](int u) {
+            wait_lgkmcnt<0>();
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_setprio(1);
+            mma(a0, b0, 2 * u);
+            mma(a1, b1, 2 * u + 1);
+            __builtin_amdgcn_s_setprio(0);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        // every wave: its share of step 0 has landed; barrier: all of step 0 has landed
+        wait_vmcnt<2 * LPT>();
+        __builtin_amdgcn_s_barrier();
+        if (grp_id == 0) {
+            if (nsteps > 0) fetch(0);
+            for (int u = 0; u < nsteps; ++u) {
+                __builtin_amdgcn_s_barrier();          // starts phase 2u
+                compute(u);
+                wait_vmcnt<2 * LPT>();                 // own share of step u+1 landed
+                __builtin_amdgcn_s_barrier();          // starts phase 2u+1: step u+1 complete, slot u free
+                if (u + 1 < nsteps) fetch(u + 1);
+            }
+        } else {
+            for (int u = 0; u < nsteps; ++u) {
+                __builtin_amdgcn_s_barrier();          // starts phase 2u
+                fetch(u);
+                wait_vmcnt<2 * LPT>();
+                wait_lgkmcnt<0>();                     // own reads of slot u done before group 0 may refill it
+                __builtin_amdgcn_s_barrier();          // starts phase 2u+1
+                compute(u);
+            }
+        }
+        wait_vmcnt<0>();
+    } else {
     for (int u = 0; u < nsteps; ++u) {
         const int slot = u & (STAGES - 1);
         wait_vmcnt<2 * LPT>();
@@ -348,6 +398,7 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
     wait_lgkmcnt<0>();
     __builtin_amdgcn_sched_barrier(0);
     if (nsteps > 0) mma(a1, b1, 2 * (nsteps - 1) + 1);
+    }
     __syncthreads();
 
     // ------------------------------------------------------------------------------ epilogues
