@@ -334,10 +334,10 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
         // instructions of the other wave issue in its shadow.
         const int grp_id = wave >> 2;
         auto fetch = [&](int u) {   // fragments of step u -> registers; refill the slot step u-1 used
-            const int slot = u & (STAGES - 1);
+            const int slot = u % STAGES;
             frags(a0, b0, slot, 0);
             frags(a1, b1, slot, 1);
-            issue((u + STAGES - 1) & (STAGES - 1));
+            issue((u + STAGES - 1) % STAGES);
             advance();
         };
         auto compute = [&](int u) {
@@ -350,14 +350,14 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
             __builtin_amdgcn_sched_barrier(0);
         };
         // every wave: its share of step 0 has landed; barrier: all of step 0 has landed
-        wait_vmcnt<2 * LPT>();
+        wait_vmcnt<(STAGES - 2) * LPT>();
         __builtin_amdgcn_s_barrier();
         if (grp_id == 0) {
             if (nsteps > 0) fetch(0);
             for (int u = 0; u < nsteps; ++u) {
                 __builtin_amdgcn_s_barrier();          // starts phase 2u
                 compute(u);
-                wait_vmcnt<2 * LPT>();                 // own share of step u+1 landed
+                wait_vmcnt<(STAGES - 2) * LPT>();                 // own share of step u+1 landed
                 __builtin_amdgcn_s_barrier();          // starts phase 2u+1: step u+1 complete, slot u free
                 if (u + 1 < nsteps) fetch(u + 1);
             }
@@ -365,7 +365,7 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
             for (int u = 0; u < nsteps; ++u) {
                 __builtin_amdgcn_s_barrier();          // starts phase 2u
                 fetch(u);
-                wait_vmcnt<2 * LPT>();
+                wait_vmcnt<(STAGES - 2) * LPT>();
                 wait_lgkmcnt<0>();                     // own reads of slot u done before group 0 may refill it
                 __builtin_amdgcn_s_barrier();          // starts phase 2u+1
                 compute(u);
@@ -374,8 +374,8 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
         wait_vmcnt<0>();
     } else {
     for (int u = 0; u < nsteps; ++u) {
-        const int slot = u & (STAGES - 1);
-        wait_vmcnt<2 * LPT>();
+        const int slot = u % STAGES;
+        wait_vmcnt<(STAGES - 2) * LPT>();
         // A bare s_barrier: __syncthreads() would also fence, i.e. wait for every load still in
         // flight to the other ring slots.  What must be complete here is only this wave's share of
         // step u (the vmcnt wait above) and its LDS reads of step u-1 (lgkmcnt).
@@ -383,7 +383,7 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
         __builtin_amdgcn_s_barrier();
         frags(a0, b0, slot, 0);
         __builtin_amdgcn_sched_barrier(0);
-        issue((u + STAGES - 1) & (STAGES - 1));
+        issue((u + STAGES - 1) % STAGES);
         if (u > 0) mma(a1, b1, 2 * (u - 1) + 1);   // its fragments were complete before the barrier
         __builtin_amdgcn_sched_barrier(0);
         frags(a1, b1, slot, 1);
