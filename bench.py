@@ -46,6 +46,7 @@ def kernel_work(cfg):
         "gemm_dx": (2.0 * T * di * (do + r), e * (T * do + do * di + T * r + r * di + T * di)),
         "gemm_dA": (2.0 * r * di * T, e * (T * r + T * di) + 4 * r * di),
         "gemm_dB": (2.0 * do * r * T, e * (T * do + T * r) + 4 * do * r),
+        "gemm_fused_fwd": (2.0 * T * do * (di + r), e * (T * di + do * di + T * r + do * r + 2 * T * do)),
     }
 
 
@@ -95,6 +96,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="C3", choices=["C2", "C3"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--fused-forward", action="store_true",
+                    help="forward through dora_forward_fused (compose folded into the GEMM epilogue) instead of the\n"
+                         "base / lora / compose sequence")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -125,8 +129,10 @@ def main():
     ws_f = G.workspace(desc, D.PHASE_FORWARD)
     ws_b = G.workspace(desc, D.PHASE_BACKWARD)
 
+    fwd = D.dora_forward_fused if args.fused_forward else D.dora_forward
+
     def step():
-        D.dora_forward(desc, mod.x, mod.W, mod.A, mod.B, mod.m, None, y, h, inner, c, ws_f)
+        fwd(desc, mod.x, mod.W, mod.A, mod.B, mod.m, None, y, h, inner, c, ws_f)
         D.dora_backward(desc, mod.dy, mod.x, mod.W, mod.A, mod.B, mod.m, c, h, inner, dx, dA, dB, dm, ws_b)
 
     for _ in range(args.warmup):
@@ -147,13 +153,27 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
     # the same number of steps without the event pairs, to show what they cost
-    torch.cuda.synchronize()
-    t2 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t3 = time.perf_counter()
-    ms_untraced = (t3 - t2) * 1e3 / args.steps
+    def timed(fn):
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - a) * 1e3 / args.steps
+
+    ms_untraced = timed(step)
+
+    # the other forward path (compose folded into the GEMM epilogue when the default is timed, and the
+    # other way round), same backward, no event pairs: reported beside `value`, not instead of it
+    other_fwd = D.dora_forward if args.fused_forward else D.dora_forward_fused
+
+    def other_step():
+        other_fwd(desc, mod.x, mod.W, mod.A, mod.B, mod.m, None, y, h, inner, c, ws_f)
+        D.dora_backward(desc, mod.dy, mod.x, mod.W, mod.A, mod.B, mod.m, c, h, inner, dx, dA, dB, dm, ws_b)
+
+    for _ in range(2):
+        other_step()
+    ms_other = timed(other_step)
 
     # what this card sustains with no other work in the way: a plain streaming copy and a
     # register-resident MFMA loop, timed the same way (library events on the launch stream)
@@ -190,7 +210,7 @@ def main():
         if D.dora_trace_get(names.index(guest))[1] == 0:
             work[host] = (work[host][0] + work[guest][0], work[host][1] + work[guest][1])
     kernels = []
-    for kid in range(16):
+    for kid in list(range(16)) + [18]:
         total_ms, n = D.dora_trace_get(kid)
         if n == 0:
             continue
@@ -217,12 +237,15 @@ def main():
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": cfg.name, "d_out": do, "d_in": di, "r": r, "tokens": T,
-                   "phase": "forward (saves h, inner, w_norm) + backward (dx, dA, dB, dm)"},
+                   "phase": "forward (saves h, inner, w_norm) + backward (dx, dA, dB, dm)",
+                   "forward_path": "fused epilogue" if args.fused_forward else "base, lora, compose pass"},
         "roofline": roofline,
         "mfma_frac_all_contractions": mfma_flops / mfma_time / 1e12 / PEAK_BF16_TFLOPS,
-        "hbm_frac_compose_fwd": next(k["frac"] for k in kernels if k["kernel"] == "compose_fwd"),
+        "hbm_frac_compose_fwd": next((k["frac"] for k in kernels if k["kernel"] == "compose_fwd"), None),
         "hbm_frac_compose_bwd": next(k["frac"] for k in kernels if k["kernel"] == "compose_bwd"),
         "ms_per_step_without_event_pairs": ms_untraced,
+        "other_forward_path": {"forward_path": "base, lora, compose pass" if args.fused_forward else "fused epilogue",
+                               "ms_per_step_without_event_pairs": ms_other, "tokens_per_s": T / (ms_other * 1e-3)},
         "sustained_on_this_card": sustained,
         "workspace_bytes": {"norm": D.dora_workspace_bytes(desc, D.PHASE_NORM),
                             "forward": D.dora_workspace_bytes(desc, D.PHASE_FORWARD),

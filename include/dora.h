@@ -131,6 +131,19 @@ dora_status dora_forward(const dora_desc* desc, const void* x, const void* W, co
                          void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Same result as dora_forward, computed without the base / lora round trip: one K-concatenated
+ * contraction  inner = [s*h | x] [B | W]^T  (the low-rank segment first, its accumulators multiplied
+ * by s, then the d_in segment on top) whose epilogue writes y = g (.) inner and, if asked, inner.
+ * The cancellation issue of Sec. 3.1 concerns the *delta* form only; g (.) inner taken from an fp32
+ * accumulator has none.  DORA_BF16 descs only (DORA_ERR_DTYPE otherwise).  Arguments, workspace
+ * (DORA_PHASE_FORWARD) and saved tensors exactly as for dora_forward.
+ */
+dora_status dora_forward_fused(const dora_desc* desc, const void* x, const void* W, const void* A,
+                               const void* B, const float* m, const float* w_norm,
+                               void* y, void* saved_h, void* saved_inner, float* w_norm_out,
+                               void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Backward of the module with the norm held constant (Sec. 2.2; App. A item 2) and W frozen:
  *   dz = g (.) dy;  dh = s * dz B;  dx = dz W + dh A;  dA = dh^T x;  dB = s * dz^T h;
  *   dm as in dora_compose_backward.
@@ -176,7 +189,8 @@ enum {
     DORA_K_GEMM_DB = 15,     /* dB = s dz^T h                                          */
     DORA_K_PROBE_COPY = 16,  /* dora_probe_copy                                        */
     DORA_K_PROBE_MFMA = 17,  /* dora_probe_mfma                                        */
-    DORA_K_COUNT = 18
+    DORA_K_GEMM_FUSED_FWD = 18, /* y = g (.) ([s*h | x] [B | W]^T), dora_forward_fused  */
+    DORA_K_COUNT = 19
 };
 void dora_trace_enable(int on);
 void dora_trace_reset(void);

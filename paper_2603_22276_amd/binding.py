@@ -16,11 +16,11 @@ LIB_PATH = os.path.join(HERE, "libdora.so")
 
 DORA_F32, DORA_BF16 = 0, 1
 PHASE_NORM, PHASE_FORWARD, PHASE_BACKWARD, PHASE_BACKWARD_RECOMPUTE, PHASE_COMPOSE_BACKWARD = range(5)
-K_COUNT = 18
+K_COUNT = 19
 
 EXPORTS = (
     "dora_workspace_bytes", "dora_norm", "dora_mag_scale", "dora_compose", "dora_compose_backward",
-    "dora_project", "dora_forward", "dora_backward", "dora_status_str",
+    "dora_project", "dora_forward", "dora_forward_fused", "dora_backward", "dora_status_str",
     "dora_probe_copy", "dora_probe_mfma",
     "dora_trace_enable", "dora_trace_reset", "dora_trace_collect", "dora_trace_get", "dora_trace_name",
 )
@@ -59,10 +59,11 @@ def lib() -> ctypes.CDLL:
         L.dora_compose_backward.argtypes = [dp, vp, vp, fp, fp, vp, fp, vp, sz, vp]
         L.dora_project.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.dora_forward.argtypes = [dp, vp, vp, vp, vp, fp, fp, vp, vp, vp, fp, vp, sz, vp]
+        L.dora_forward_fused.argtypes = L.dora_forward.argtypes
         L.dora_backward.argtypes = [dp, vp, vp, vp, vp, vp, fp, fp, vp, vp, vp, fp, fp, fp, vp, sz, vp]
         L.dora_probe_copy.argtypes = [vp, vp, sz, vp]
         L.dora_probe_mfma.argtypes = [fp, ctypes.c_int, ctypes.c_int, vp]
-        for f in (L.dora_probe_copy, L.dora_probe_mfma, L.dora_norm, L.dora_mag_scale, L.dora_compose, L.dora_compose_backward, L.dora_project, L.dora_forward,
+        for f in (L.dora_probe_copy, L.dora_probe_mfma, L.dora_norm, L.dora_mag_scale, L.dora_compose, L.dora_compose_backward, L.dora_project, L.dora_forward, L.dora_forward_fused,
                   L.dora_backward, L.dora_trace_collect, L.dora_trace_get):
             f.restype = ctypes.c_int
         L.dora_status_str.argtypes = [ctypes.c_int]
@@ -149,6 +150,12 @@ def dora_project(desc, x, W, A, B, base, h, lora, stream=None) -> None:
 def dora_forward(desc, x, W, A, B, m, w_norm, y, saved_h, saved_inner, w_norm_out, ws, stream=None) -> None:
     _check(lib().dora_forward(ctypes.byref(desc), _p(x), _p(W), _p(A), _p(B), _p(m), _p(w_norm), _p(y), _p(saved_h),
                               _p(saved_inner), _p(w_norm_out), _p(ws), _nbytes(ws), _stream(stream)), "dora_forward")
+
+
+def dora_forward_fused(desc, x, W, A, B, m, w_norm, y, saved_h, saved_inner, w_norm_out, ws, stream=None) -> None:
+    _check(lib().dora_forward_fused(ctypes.byref(desc), _p(x), _p(W), _p(A), _p(B), _p(m), _p(w_norm), _p(y),
+                                    _p(saved_h), _p(saved_inner), _p(w_norm_out), _p(ws), _nbytes(ws),
+                                    _stream(stream)), "dora_forward_fused")
 
 
 def dora_backward(desc, dy, x, W, A, B, m, w_norm, saved_h, saved_inner, dx, dA, dB, dm, ws, stream=None) -> None:

@@ -53,7 +53,8 @@ struct TraceScope {
 enum GemmEpilogue {
     EPI_STORE_BF16 = 0,  // C bf16 [M, ldc]
     EPI_STORE_F32 = 1,   // C fp32 [M, ldc]; with ksplit > 1 slice z goes to C + z*M*ldc
-    EPI_ROWDOT = 2       // no C; partial[z*tiles_n + tn][m] = sum_n acc[m,n] * R[m,n]  (+ base_sq of Aop rows)
+    EPI_ROWDOT = 2,      // no C; partial[z*tiles_n + tn][m] = sum_n acc[m,n] * R[m,n]  (+ base_sq of Aop rows)
+    EPI_COMPOSE = 3      // C bf16 = colscale[n] * acc; optionally C2 bf16 = acc (the compose folded into the epilogue)
 };
 
 struct GemmSeg {
@@ -74,6 +75,10 @@ struct GemmArgs {
     int64_t ldc;
     int ksplit;                // split of segment 0's K range (nseg must be 1 when > 1)
     int tag;                   // 0 or 1: selects a differently named (otherwise identical) kernel instance
+    float seg0_scale;          // accumulators are multiplied by this once segment 0 is done (0 = off)
+    // EPI_COMPOSE only
+    const float* colscale;     // [N] fp32
+    void* c2;                  // second output [M, ldc] bf16 (unscaled accumulator) or nullptr
     // EPI_ROWDOT only
     const bf16_t* rowdot;      // R [M, ld_rowdot] bf16
     int64_t ld_rowdot;

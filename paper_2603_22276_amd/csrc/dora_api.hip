@@ -452,6 +452,49 @@ dora_status dora_forward(const dora_desc* desc, const void* x, const void* W, co
     return DORA_OK;
 }
 
+dora_status dora_forward_fused(const dora_desc* desc, const void* x, const void* W, const void* A, const void* B,
+                               const float* m, const float* w_norm, void* y, void* saved_h, void* saved_inner,
+                               float* w_norm_out, void* ws, size_t ws_bytes, void* stream)
+{
+    dora_status st = check_desc(desc, true);
+    if (st != DORA_OK) return st;
+    if (desc->dtype != DORA_BF16) return DORA_ERR_DTYPE;
+    DORA_REQ_PTR(W); DORA_REQ_PTR(A); DORA_REQ_PTR(B); DORA_REQ_PTR(m);
+    if (desc->tokens > 0) { DORA_REQ_PTR(x); DORA_REQ_PTR(y); }
+    DORA_OPT_PTR(w_norm); DORA_OPT_PTR(saved_h); DORA_OPT_PTR(saved_inner); DORA_OPT_PTR(w_norm_out);
+    const bool need_norm = (w_norm == nullptr);
+    Bump sizing(nullptr);
+    FwdPlan p;
+    plan_fwd(desc, sizing, p, need_norm, saved_h == nullptr, false);
+    if ((st = check_ws(ws, ws_bytes, sizing.off)) != DORA_OK) return st;
+    Bump b(ws);
+    plan_fwd(desc, b, p, need_norm, saved_h == nullptr, false);
+    hipStream_t s = (hipStream_t)stream;
+    const int T = (int)desc->tokens, d_out = (int)desc->d_out, d_in = (int)desc->d_in, r = (int)desc->r;
+
+    const float* c = w_norm;
+    if (need_norm) {
+        float* cw = w_norm_out ? w_norm_out : p.c;
+        if ((st = norm_impl(desc, W, A, B, cw, p.norm, s)) != DORA_OK) return st;
+        c = cw;
+    } else if (w_norm_out && w_norm_out != w_norm) {
+        DORA_HIP(hipMemcpyAsync(w_norm_out, w_norm, sizeof(float) * d_out, hipMemcpyDeviceToDevice, s));
+    }
+    if (T == 0) return DORA_OK;
+    DORA_HIP(launch_mag_scale(m, c, eff_eps(desc), p.g, nullptr, d_out, s));
+    void* h = saved_h ? saved_h : p.h;
+    Seg s1{x, d_in, A, d_in, d_in};
+    DORA_HIP(contract(DORA_BF16, true, true, T, r, &s1, 1, 1.f, h, r, false, DORA_K_GEMM_H, s));
+    Seg segs[2] = {{h, r, B, r, r}, {x, d_in, W, d_in, d_in}};
+    GemmArgs g = bf16_args(true, true, T, d_out, segs, 2, 1.f, y, d_out, false, 0);
+    g.epilogue = EPI_COMPOSE;
+    g.seg0_scale = desc->s;
+    g.colscale = p.g;
+    g.c2 = saved_inner;
+    DORA_HIP(launch_gemm_bf16(g, DORA_K_GEMM_FUSED_FWD, s));
+    return DORA_OK;
+}
+
 dora_status dora_backward(const dora_desc* desc, const void* dy, const void* x, const void* W, const void* A,
                           const void* B, const float* m, const float* w_norm, const void* saved_h,
                           const void* saved_inner, void* dx, float* dA, float* dB, float* dm, void* ws,
@@ -586,7 +629,7 @@ const char* dora_trace_name(int kernel_id)
     static const char* names[DORA_K_COUNT] = {
         "norm_cross_WAt", "gram_AAt", "gram_reduce", "ba_sq_BGB", "norm_final", "mag_scale", "gemm_base_xWt",
         "gemm_h_xAt", "gemm_lora_hBt", "compose_fwd", "compose_bwd", "dm_final", "gemm_dh_dzB", "gemm_dx",
-        "gemm_dA", "gemm_dB", "probe_copy", "probe_mfma"};
+        "gemm_dA", "gemm_dB", "probe_copy", "probe_mfma", "gemm_fused_fwd"};
     return (kernel_id >= 0 && kernel_id < DORA_K_COUNT) ? names[kernel_id] : "?";
 }
 

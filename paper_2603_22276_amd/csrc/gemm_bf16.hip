@@ -240,6 +240,19 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
 #pragma unroll
     for (int i = 0; i < MT; ++i) bsq[i] = 0.f;
     const bool want_bsq = (EPI == EPI_ROWDOT) && (p.base_sq_partial != nullptr) && (tc.tn == 0);
+    // K steps of segment 0 inside this workgroup's range; when they are done the accumulators may be
+    // rescaled once (used to apply s to the low-rank segment of the K-concatenated forward)
+    const int seg0_steps = (t_end < kt0_total ? t_end : kt0_total) - t_begin;
+    const bool rescale = (p.seg0_scale != 0.f) && (p.nseg > 1);
+    auto rescale_acc = [&]() {
+        const float f = p.seg0_scale;
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] *= f;
+    };
 
     typedef OperandLoader<BM, T::NLA, T::WAVES, A_KC> LA;
     typedef OperandLoader<BN, T::NLB, T::WAVES, B_KC> LB;
@@ -348,6 +361,7 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
             mma(a1, b1, 2 * u + 1);
             __builtin_amdgcn_s_setprio(0);
             __builtin_amdgcn_sched_barrier(0);
+            if (rescale && u == seg0_steps - 1) rescale_acc();
         };
         // every wave: its share of step 0 has landed; barrier: all of step 0 has landed
         wait_vmcnt<(STAGES - 2) * LPT>();
@@ -385,6 +399,7 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
         __builtin_amdgcn_sched_barrier(0);
         issue((u + STAGES - 1) % STAGES);
         if (u > 0) mma(a1, b1, 2 * (u - 1) + 1);   // its fragments were complete before the barrier
+        if (rescale && u == seg0_steps) rescale_acc();   // step u-1 was the last of segment 0
         __builtin_amdgcn_sched_barrier(0);
         frags(a1, b1, slot, 1);
         __builtin_amdgcn_sched_barrier(0);
@@ -443,13 +458,27 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
 
     // STORE: stage each 32-row band of the wave's sub-tile through LDS, then write whole 16-byte
     // vectors along N.
-    constexpr bool OUT_BF16 = (EPI == EPI_STORE_BF16);
+    constexpr bool OUT_BF16 = (EPI == EPI_STORE_BF16) || (EPI == EPI_COMPOSE);
     constexpr int ESZ = OUT_BF16 ? 2 : 4;
     constexpr int ROW_BYTES = T::WN * ESZ + 16;
     constexpr int CHUNKS_PER_ROW = T::WN * ESZ / 16;
     constexpr int ROWS_PER_PASS = 64 / CHUNKS_PER_ROW;
     char* stg = smem + wave * T::EPI_BYTES_PER_WAVE;
-    char* cbase = reinterpret_cast<char*>(p.c) + (p.ksplit > 1 ? (int64_t)tc.z * p.M * p.ldc * ESZ : 0);
+    // EPI_COMPOSE: pass 0 writes colscale[n] * acc to C (y = g (.) inner), pass 1 writes acc to C2 (inner)
+    float4 cs[NT][4];
+    if (EPI == EPI_COMPOSE) {
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int ng = n0 + wn0 + j * 32 + b * 8 + lh * 4;
+                cs[j][b] = (ng < p.N) ? *reinterpret_cast<const float4*>(p.colscale + ng) : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+    }
+    const int npass = (EPI == EPI_COMPOSE && p.c2 != nullptr) ? 2 : 1;
+    for (int pass = 0; pass < npass; ++pass) {
+    char* cbase = reinterpret_cast<char*>(pass == 0 ? p.c : p.c2) +
+                  (p.ksplit > 1 ? (int64_t)tc.z * p.M * p.ldc * ESZ : 0);
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
         __builtin_amdgcn_wave_barrier();
@@ -458,8 +487,15 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 const int col = j * 32 + b * 8 + lh * 4;
-                float v0 = p.alpha * acc[i][j][b * 4 + 0], v1 = p.alpha * acc[i][j][b * 4 + 1];
-                float v2 = p.alpha * acc[i][j][b * 4 + 2], v3 = p.alpha * acc[i][j][b * 4 + 3];
+                float v0, v1, v2, v3;
+                if (EPI == EPI_COMPOSE) {
+                    const float4 g4 = (pass == 0) ? cs[j][b] : make_float4(1.f, 1.f, 1.f, 1.f);
+                    v0 = g4.x * acc[i][j][b * 4 + 0]; v1 = g4.y * acc[i][j][b * 4 + 1];
+                    v2 = g4.z * acc[i][j][b * 4 + 2]; v3 = g4.w * acc[i][j][b * 4 + 3];
+                } else {
+                    v0 = p.alpha * acc[i][j][b * 4 + 0]; v1 = p.alpha * acc[i][j][b * 4 + 1];
+                    v2 = p.alpha * acc[i][j][b * 4 + 2]; v3 = p.alpha * acc[i][j][b * 4 + 3];
+                }
                 if (OUT_BF16) {
                     uint2 o;
                     o.x = pack_bf16x2(v0, v1);
@@ -480,6 +516,7 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
             if (mg < p.M && ng < p.N)
                 *reinterpret_cast<uint4*>(cbase + ((int64_t)mg * p.ldc + ng) * ESZ) = v;
         }
+    }
     }
 }
 
@@ -510,7 +547,7 @@ bool use_big(const GemmArgs& a)
 {
     // the large tile pays off once it still yields a few tiles per CU
     int64_t big_tiles = (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256);
-    return a.epilogue == EPI_STORE_BF16 && a.ksplit == 1 && big_tiles >= 256;
+    return (a.epilogue == EPI_STORE_BF16 || a.epilogue == EPI_COMPOSE) && a.ksplit == 1 && big_tiles >= 256;
 }
 
 hipError_t dispatch(const GemmArgs& a, const GemmArgs* b, hipStream_t stream)
@@ -521,6 +558,7 @@ hipError_t dispatch(const GemmArgs& a, const GemmArgs* b, hipStream_t stream)
         return big ? launch_one<TileBig, AKC, BKC, E>(a, b, stream) : launch_one<TileMed, AKC, BKC, E>(a, b, stream);
     DORA_GEMM_CASE(true, true, EPI_STORE_BF16)
     DORA_GEMM_CASE(true, false, EPI_STORE_BF16)
+    DORA_GEMM_CASE(true, true, EPI_COMPOSE)
 #undef DORA_GEMM_CASE
 #define DORA_GEMM_CASE_MED(AKC, BKC, E)                                                 \
     if (a.a_kcontig == (AKC) && a.b_kcontig == (BKC) && a.epilogue == (E))              \

@@ -297,3 +297,39 @@ def test_probes_run_and_copy_is_exact():
     D.dora_probe_mfma(sink, 4, 8)
     torch.cuda.synchronize()
     assert float(sink.abs().max()) == 0.0
+
+
+BF16_CASES = [c for c in SMALL if c.dtype == "bf16"]
+
+
+@pytest.mark.parametrize("cfg", BF16_CASES, ids=[c.name for c in BF16_CASES])
+def test_fused_forward_matches_oracle_and_contract_path(cfg):
+    # K-concatenated forward with the compose folded into the MFMA epilogue
+    mod = G.Module(cfg)
+    f = O.forward(**oracle_inputs(mod))
+    tol = G.TOL["bf16"]["tensor"]
+    out = mod.forward(fused=True)
+    G.assert_norm_close(G.to_f64(out["c"]), f["c"], G.TOL["bf16"]["norm"])
+    G.assert_close("y", G.to_f64(out["y"]), f["y"], tol)
+    G.assert_close("inner", G.to_f64(out["inner"]), f["inner"], tol)
+    G.assert_close("h", G.to_f64(out["h"]), f["h"], tol)
+    # it rounds once from the fp32 accumulator: at least as close to the oracle as the two-pass path
+    ref = mod.forward()
+    e_fused = G.rel_fro(G.to_f64(out["y"]), f["y"])
+    e_two = G.rel_fro(G.to_f64(ref["y"]), f["y"])
+    assert e_fused <= 1.05 * e_two + 1e-6
+    # without saved tensors, and with a supplied norm: same y
+    out2 = mod.forward(fused=True, save=False, w_norm=out["c"])
+    assert torch.equal(out2["y"].view(torch.uint8), out["y"].view(torch.uint8))
+    # the saved tensors drive the backward as usual
+    b = O.backward(mod.f64("dy"), **oracle_inputs(mod))
+    grads = mod.backward(w_norm=out["c"], h=out["h"], inner=out["inner"])
+    for k in ("dx", "dA", "dB", "dm"):
+        G.assert_close(k, G.to_f64(grads[k]), b[k], tol)
+
+
+def test_fused_forward_rejects_fp32():
+    mod = G.Module(I.C1)
+    with pytest.raises(D.DoraError) as e:
+        mod.forward(fused=True)
+    assert e.value.status == 4
