@@ -111,8 +111,9 @@ struct Bump {
     }
 };
 
-// Split-K factors of the two norm contractions: enough workgroups to cover 256 CUs twice over
-// (two of the 128x128-tile workgroups fit a CU), bounded so the partials stay small.
+// Split-K factors of the two norm contractions: as many workgroups as fit the chip in ONE round
+// (256 CUs x two 128x128-tile workgroups each = 512 slots; a 513th would add a whole extra round),
+// bounded so the partials stay small.
 constexpr int TILE = 128;
 inline int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
@@ -133,12 +134,12 @@ void plan_norm(const dora_desc* d, Bump& b, NormPlan& n)
     const int ktiles = cdiv(d->d_in, 64);
     n.tiles_n = cdiv(d->r, TILE);
     const int tiles_u = cdiv(d->d_out, TILE) * n.tiles_n;
-    n.ks_u = cdiv(512, tiles_u);
+    n.ks_u = 512 / tiles_u;
     if (n.ks_u > 8) n.ks_u = 8;
     if (n.ks_u > ktiles) n.ks_u = ktiles;
     if (n.ks_u < 1) n.ks_u = 1;
     const int tiles_g = n.tiles_n * n.tiles_n;
-    n.ks_g = cdiv(512, tiles_g);
+    n.ks_g = 512 / tiles_g;
     if (n.ks_g > 16) n.ks_g = 16;
     if (n.ks_g > ktiles) n.ks_g = ktiles;
     if (n.ks_g < 1) n.ks_g = 1;
