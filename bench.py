@@ -139,8 +139,13 @@ def main():
         step()
     torch.cuda.synchronize()
 
-    # timed region: exactly `steps` steps, per-kernel HIP events recorded by the library on the launch stream
+    # timed region: exactly `steps` steps.  The library brackets the launches of the candidates for the
+    # dominant kernel (the two big contractions and the fused one) with HIP events on the launch stream;
+    # every other kernel is timed the same way in a second pass below, so that the throughput figure
+    # does not carry ~30 event records per step.
+    K_BASE, K_DX, K_FUSED = 6, 13, 18
     D.dora_trace_reset()
+    D.dora_trace_select((1 << K_BASE) | (1 << K_DX) | (1 << K_FUSED))
     D.dora_trace_enable(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -151,6 +156,20 @@ def main():
     D.dora_trace_enable(False)
     D.dora_trace_collect()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    dominant = {k: D.dora_trace_get(k) for k in (K_BASE, K_DX, K_FUSED)}
+
+    # second pass: every kernel bracketed (durations for the per-kernel table)
+    D.dora_trace_reset()
+    D.dora_trace_select(~0)
+    D.dora_trace_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_all_events = (time.perf_counter() - t0) * 1e3 / args.steps
+    D.dora_trace_enable(False)
+    D.dora_trace_collect()
 
     # the same number of steps without the event pairs, to show what they cost
     def timed(fn):
@@ -212,6 +231,8 @@ def main():
     kernels = []
     for kid in list(range(16)) + [18]:
         total_ms, n = D.dora_trace_get(kid)
+        if kid in dominant and dominant[kid][1] > 0:
+            total_ms, n = dominant[kid]  # the duration measured inside the timed region
         if n == 0:
             continue
         name = D.dora_trace_name(kid)
@@ -244,6 +265,7 @@ def main():
         "hbm_frac_compose_fwd": next((k["frac"] for k in kernels if k["kernel"] == "compose_fwd"), None),
         "hbm_frac_compose_bwd": next(k["frac"] for k in kernels if k["kernel"] == "compose_bwd"),
         "ms_per_step_without_event_pairs": ms_untraced,
+        "ms_per_step_with_every_kernel_bracketed": ms_all_events,
         "other_forward_path": {"forward_path": "base, lora, compose pass" if args.fused_forward else "fused epilogue",
                                "ms_per_step_without_event_pairs": ms_other, "tokens_per_s": T / (ms_other * 1e-3)},
         "sustained_on_this_card": sustained,

@@ -168,7 +168,8 @@ const char* dora_status_str(int status);
  * the launch stream.  dora_trace_collect synchronises those events and adds each launch's
  * duration to its kernel's slot; dora_trace_get reads one slot.  Kernel ids are the
  * DORA_K_* values; dora_trace_name returns a short label.  Enabling tracing creates host-side
- * event objects only (no device memory).  Not thread-safe.
+ * event objects only (no device memory).  dora_trace_select restricts the bracketing to some kernel ids, so
+ * that a throughput measurement can carry the events of its dominant kernel only.  Not thread-safe.
  */
 enum {
     DORA_K_NORM_CROSS = 0,   /* U = W A^T tile + base_sq + rowdot(B, U) partials      */
@@ -193,6 +194,7 @@ enum {
     DORA_K_COUNT = 19
 };
 void dora_trace_enable(int on);
+void dora_trace_select(uint64_t kernel_mask); /* bit k set = bracket launches of kernel id k (default: all) */
 void dora_trace_reset(void);
 int dora_trace_collect(void); /* returns a dora_status */
 int dora_trace_get(int kernel_id, double* total_ms, int64_t* launches);

@@ -22,7 +22,7 @@ EXPORTS = (
     "dora_workspace_bytes", "dora_norm", "dora_mag_scale", "dora_compose", "dora_compose_backward",
     "dora_project", "dora_forward", "dora_forward_fused", "dora_backward", "dora_status_str",
     "dora_probe_copy", "dora_probe_mfma",
-    "dora_trace_enable", "dora_trace_reset", "dora_trace_collect", "dora_trace_get", "dora_trace_name",
+    "dora_trace_enable", "dora_trace_select", "dora_trace_reset", "dora_trace_collect", "dora_trace_get", "dora_trace_name",
 )
 
 
@@ -70,6 +70,8 @@ def lib() -> ctypes.CDLL:
         L.dora_status_str.restype = ctypes.c_char_p
         L.dora_trace_enable.argtypes = [ctypes.c_int]
         L.dora_trace_enable.restype = None
+        L.dora_trace_select.argtypes = [ctypes.c_uint64]
+        L.dora_trace_select.restype = None
         L.dora_trace_reset.argtypes = []
         L.dora_trace_reset.restype = None
         L.dora_trace_collect.argtypes = []
@@ -174,6 +176,10 @@ def dora_probe_mfma(sink, iters: int, workgroups: int, stream=None) -> None:
 
 def dora_trace_enable(on: bool) -> None:
     lib().dora_trace_enable(1 if on else 0)
+
+
+def dora_trace_select(kernel_mask: int) -> None:
+    lib().dora_trace_select(int(kernel_mask) & 0xFFFFFFFFFFFFFFFF)
 
 
 def dora_trace_reset() -> None:

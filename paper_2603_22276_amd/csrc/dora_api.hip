@@ -14,6 +14,7 @@ namespace dora {
 namespace {
 struct TraceRec { int id; hipEvent_t e0, e1; };
 bool g_trace_on = false;
+uint64_t g_trace_mask = ~0ull;
 std::vector<TraceRec> g_trace_recs;          // launches since the last collect
 std::vector<hipEvent_t> g_event_pool;        // recycled events
 double g_trace_ms[DORA_K_COUNT];
@@ -29,9 +30,9 @@ hipEvent_t get_event()
 }
 }  // namespace
 
-void trace_begin(int, hipStream_t stream)
+void trace_begin(int kernel_id, hipStream_t stream)
 {
-    if (!g_trace_on) return;
+    if (!g_trace_on || !((g_trace_mask >> kernel_id) & 1ull)) return;
     g_pending_start = get_event();
     if (g_pending_start) (void)hipEventRecord(g_pending_start, stream);
 }
@@ -595,6 +596,8 @@ dora_status dora_probe_mfma(float* sink, int iters, int workgroups, void* stream
 
 // ------------------------------------------------------------------------------------------------
 void dora_trace_enable(int on) { g_trace_on = (on != 0); }
+
+void dora_trace_select(uint64_t kernel_mask) { g_trace_mask = kernel_mask; }
 
 void dora_trace_reset(void)
 {
