@@ -7,45 +7,54 @@
 // (both K-strided), and the factored-norm products of Sec. 2: U = W A^T with the row-dot epilogue
 // of Eq. 3 (U never leaves registers), G = A A^T (Eq. 4, split-K partials), and rowdot(B, B G).
 //
-// Structure (per workgroup): a BM x BN tile of C; K is walked in steps of 32 through a ring of four
-// LDS buffers that the global loads fill directly (buffer_load ... lds, 16 bytes per lane, no
-// register staging), three steps ahead of the MFMAs.  v_mfma_f32_32x32x16_bf16 on 64-wide
-// wavefronts, each wave owning a (BM/WGM) x (BN/WGN) sub-tile; operand fragments are double
-// buffered in registers so the LDS reads of one k-step overlap the MFMAs of the previous one.
-// The N-side fragment is fed as the MFMA's first operand so that every lane ends up holding four
-// consecutive n for one m, which makes the epilogue's stores and row-dots vector-friendly.
-// Workgroup ids are remapped so that each of the 8 XCDs (own L2 each) works on a compact block of
-// tiles, walked in groups of 8 tile-rows.
+// Structure (per workgroup): a BM x BN tile of C; K is walked in steps of BK through a ring of LDS
+// buffers that the global loads fill directly (buffer_load ... lds, 16 bytes per lane, no register
+// staging).  v_mfma_f32_32x32x16_bf16 on 64-wide wavefronts, each wave owning a (BM/WGM) x (BN/WGN)
+// sub-tile.  The N-side fragment is fed as the MFMA's first operand so that every lane ends up
+// holding four consecutive n for one m, which makes the epilogue's stores and row-dots
+// vector-friendly.  Workgroup ids are remapped so that each of the 8 XCDs (own L2 each) works on a
+// compact block of tiles, walked in groups of 8 tile-rows.
+//
+// Two tile shapes.  The 128 x 128 tile (4 waves, two workgroups per CU) steps K by 64, so that every
+// row segment a load instruction fetches is a full 128-byte line (64-byte segments stream at about
+// two thirds of that rate).  The 256 x 256 tile (8 waves) is bounded by LDS capacity instead: a ring
+// deep enough to cover the latency of loads that miss the L2 only fits with K steps of 32.
 #include "common.hpp"
+
+#include <type_traits>
+#include <utility>
 
 namespace dora {
 namespace {
 
-constexpr int BK = 32;          // K step per LDS buffer (elements)
-constexpr int CPR = BK / 8;     // 16-byte chunks per K-contiguous LDS row
-constexpr int STAGES = 4;       // LDS ring depth
 constexpr int NUM_XCD = 8;
 constexpr int GROUP_M = 8;
 
-template <int BM_, int BN_, int WGM_, int WGN_>
+template <int BM_, int BN_, int WGM_, int WGN_, int BK_, int STAGES_>
 struct Tile {
     static constexpr int BM = BM_, BN = BN_, WGM = WGM_, WGN = WGN_;
+    static constexpr int BK = BK_;          // K step per LDS buffer (elements)
+    static constexpr int CPR = BK / 8;      // 16-byte chunks per K-contiguous LDS row
+    static constexpr int STAGES = STAGES_;  // LDS ring depth (K steps)
     static constexpr int WAVES = WGM * WGN, THREADS = 64 * WAVES;
     static constexpr int WM = BM / WGM, WN = BN / WGN;
     static constexpr int MT = WM / 32, NT = WN / 32;
     static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-    static constexpr int NLA = BM * CPR / THREADS;  // 16-byte global loads per thread per K step, M side
+    static constexpr int NLA = BM * CPR / THREADS;  // 16-byte loads per lane per K step, M side
     static constexpr int NLB = BN * CPR / THREADS;
     static constexpr int EPI_BYTES_PER_WAVE = 32 * (WN * 4 + 16);
     static constexpr int LDS_BYTES = (STAGES * STAGE_BYTES > WAVES * EPI_BYTES_PER_WAVE) ? STAGES * STAGE_BYTES
                                                                                         : WAVES * EPI_BYTES_PER_WAVE;
+    static_assert(BK == 32 || BK == 64, "LDS layouts exist for K steps of 32 and 64");
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
+    static_assert(WAVES == 4 || WAVES == 8, "schedules exist for 4 and 8 waves");
     static_assert((BM * CPR) % THREADS == 0 && (BN * CPR) % THREADS == 0, "load plan must divide evenly");
 };
 
-typedef Tile<256, 256, 2, 4> TileBig;   // 512 threads, 128 KB of LDS, 128 accumulator registers per lane
-typedef Tile<128, 128, 2, 2> TileMed;   // 256 threads,  64 KB of LDS, two workgroups fit a CU
+typedef Tile<256, 256, 2, 4, 32, 4> TileBig;      // 512 threads, 4 x 32 KB of LDS, 128 accumulator registers per lane
+typedef Tile<128, 128, 2, 2, 64, 2> TileMed;      // 256 threads, 2 x 32 KB of LDS, two workgroups fit a CU
+typedef Tile<128, 128, 2, 2, 64, 4> TileMedDeep;  // the same with a ring of four, for launches of at most one workgroup per CU
 
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x8_t __attribute__((ext_vector_type(8)));
@@ -53,16 +62,23 @@ typedef uint64_t u64x1_t;
 typedef uint64_t u64x2_t __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) void* lds_void_ptr_t;
 
-// The LDS has 64 banks of 4 bytes and serves a 16-byte-per-lane access 16 lanes at a time, so 16
-// consecutive lanes must touch 16 different 16-byte slots modulo 256 bytes.
+// The LDS serves a 16-byte-per-lane access 16 lanes at a time, and those 16 lanes must touch 16
+// different 16-byte slots modulo 256 bytes.
 //
-// K-contiguous operand: [rows][BK] bf16, 64 bytes per row, chunk index XORed with row/4: the 16 rows
-// one group of lanes reads (same logical chunk) then cover all 16 slots.
+// K-contiguous operand: [rows][BK] bf16.  With 128-byte rows (BK = 64) the chunk index is XORed with
+// row/2, with 64-byte rows (BK = 32) with row/4: the 16 rows one group of lanes reads (same logical
+// chunk) then cover all 16 slots.
+template <int BK>
+__device__ __forceinline__ int kc_swizzle(int row)
+{
+    return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3);
+}
+template <int BK>
 __device__ __forceinline__ int lds_off(int row, int k)
 {
-    return row * (BK * 2) + ((((k >> 3) ^ (row >> 2)) & (CPR - 1)) << 4) + ((k & 7) << 1);
+    return row * (BK * 2) + ((((k >> 3) ^ kc_swizzle<BK>(row)) & (BK / 8 - 1)) << 4) + ((k & 7) << 1);
 }
-// K-strided operand: kept as loaded, [BK][ROWS] bf16; chunks of 8 rows XORed with 4*(k mod 4) so the
+// K-strided operand: kept as loaded, [BK][ROWS] bf16 (the layout does not depend on BK); chunks of 8 rows XORed with 4*(k mod 4) so the
 // four k-rows one transposing read touches fall into different slots.
 template <int ROWS>
 __device__ __forceinline__ int lds_off_ks(int row, int k)
@@ -71,39 +87,65 @@ __device__ __forceinline__ int lds_off_ks(int row, int k)
     return k * (ROWS * 2) + ((((row >> 3) ^ ((k & 3) << 2))) << 4) + ((row & 7) << 1);
 }
 
-// MFMA operand fragment for the 32 rows starting at `row0` and the 16 k starting at k16*16:
-// lane l gets row row0 + (l & 31), k = k16*16 + 8*(l >> 5) + 0..7.
-template <int ROWS, bool KCONTIG>
-__device__ __forceinline__ bf16x8_t load_frag(const char* tile, int row0, int k16, int lane)
+// Compile-time loop: f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N - 1>{})
+template <class F, int... Is>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, Is...>)
 {
-    if (KCONTIG) {
-        return *reinterpret_cast<const bf16x8_t*>(tile + lds_off(row0 + (lane & 31), k16 * 16 + (lane >> 5) * 8));
-    } else {
-        // ds_read_b64_tr_b16: inside each block of 16 lanes, lane i receives element (i & 3) of the
-        // 8 bytes addressed by lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12.  Lane L therefore points at
-        // k-row (L & 15) / 4 and rows 4*(L & 3) .. +3 of its block; blocks 1 and 3 sit 16 rows further,
-        // blocks 2 and 3 eight k further.
-        const int row = row0 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
-        const int k = k16 * 16 + (lane >> 5) * 8 + ((lane & 15) >> 2);
-        // Issued as inline assembly: the compiler otherwise makes this read wait for every global
-        // load still in flight to the other ring slots.  The caller waits on lgkmcnt before use.
-        typedef __attribute__((address_space(3))) const char* lds_cptr_t;
-        const uint32_t addr = (uint32_t)(uintptr_t)(lds_cptr_t)(tile + lds_off_ks<ROWS>(row, k));
-        u64x1_t lo, hi;
-        asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(addr));
-        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(addr), "n"(4 * ROWS * 2));  // k + 4: same swizzle
-        u64x2_t v = {lo, hi};
-        return __builtin_bit_cast(bf16x8_t, v);
-    }
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// LDS reads are issued as inline assembly with immediate offsets: the compiler neither tracks them in
+// lgkmcnt nor makes them wait for global -> LDS loads still in flight to other ring slots, so every
+// consumer is preceded by an explicit wait_lgkmcnt.
+template <int OFF>
+__device__ __forceinline__ bf16x8_t lds_read_b128(uint32_t addr)
+{
+    static_assert(OFF >= 0 && OFF < 65536, "ds_read offset field is 16 bits");
+    bf16x8_t v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+// Two transposing reads (k and k + 4 of a K-strided tile, HI bytes apart) forming one MFMA fragment.
+// ds_read_b64_tr_b16: inside each block of 16 lanes, lane i receives element (i & 3) of the 8 bytes
+// addressed by lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12.
+template <int OFF, int HI>
+__device__ __forceinline__ bf16x8_t lds_read_tr(uint32_t addr)
+{
+    static_assert(OFF >= 0 && OFF + HI < 65536, "ds_read offset field is 16 bits");
+    u64x1_t lo, hi;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(addr), "n"(OFF));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(addr), "n"(OFF + HI));
+    u64x2_t v = {lo, hi};
+    return __builtin_bit_cast(bf16x8_t, v);
+}
+
+// Byte offset, inside an operand's LDS tile, that lane `lane` reads for the MFMA fragment of the 32
+// rows starting at row0: the lane gets row row0 + (lane & 31), k = k16*16 + 8*(lane >> 5) + 0..7.
+// K-contiguous tile: one 16-byte read.  K-strided tile: the lane points at k-row
+// k16*16 + 8*(lane >> 5) + (lane & 15) / 4 and rows 4*(lane & 3) .. +3 of its 16-lane block; blocks 1
+// and 3 sit 16 rows further; the second read takes k + 4 (same swizzle).
+template <int ROWS, int BK, bool KCONTIG>
+__device__ __forceinline__ uint32_t frag_off(int row0, int k16, int lane)
+{
+    if (KCONTIG) return (uint32_t)lds_off<BK>(row0 + (lane & 31), k16 * 16 + (lane >> 5) * 8);
+    return (uint32_t)lds_off_ks<ROWS>(row0 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4,
+                                      k16 * 16 + (lane >> 5) * 8 + ((lane & 15) >> 2));
 }
 
 // Global -> LDS for one [ROWS x BK] operand tile.  Each wave-wide load instruction fills 1 KB of
 // contiguous LDS (lane i lands at byte 16*i of it), so lane i fetches from global memory whatever
-// belongs at that position of the swizzled tile.  Loads go through a buffer descriptor: an offset at
-// or beyond num_records yields zeros, which covers rows past the end of the operand; rows or k out
-// of range for other reasons get the offset 0xFFFFFFFF.  The K advance travels in the scalar offset.
-template <int ROWS, int NL, int WAVES, bool KCONTIG>
+// belongs at that position of the swizzled tile; consecutive lanes cover one row segment of 2*BK bytes.
+// Loads go through a buffer descriptor: an offset at or beyond num_records yields zeros, which
+// covers rows past the end of the operand; rows or k out of range for other reasons get the offset
+// 0xFFFFFFFF.  The K advance travels in the scalar offset.  The LW waves of the workgroup share the tile.
+template <int ROWS, int BK, int NL, int LW, bool KCONTIG>
 struct OperandLoader {
+    static constexpr int CPR = BK / 8;
     static __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const bf16_t* base, int64_t ld, int rows, int K)
     {
         int64_t elems = KCONTIG ? ((int64_t)(rows - 1) * ld + K) : ((int64_t)(K - 1) * ld + rows);
@@ -111,41 +153,47 @@ struct OperandLoader {
         return __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(base), 0, (int)(uint32_t)(elems * 2), 0x00020000);
     }
     // tile-local (row, k) of the chunk that load i of this lane brings in
-    static __device__ __forceinline__ void chunk_of(int i, int wave, int lane, int& row, int& k)
+    static __device__ __forceinline__ void chunk_of(int i, int lw, int lane, int& row, int& k)
     {
-        const int pos = (i * WAVES + wave) * 64 + lane;  // chunk position in the LDS tile
+        const int pos = (i * LW + lw) * 64 + lane;  // chunk position in the LDS tile
         if (KCONTIG) {
             row = pos / CPR;
-            k = (((pos % CPR) ^ (row >> 2)) & (CPR - 1)) * 8;
+            k = (((pos % CPR) ^ kc_swizzle<BK>(row)) & (CPR - 1)) * 8;
         } else {
             k = pos / (ROWS / 8);
             row = ((pos % (ROWS / 8)) ^ ((k & 3) << 2)) * 8;
         }
     }
-    // per-lane constants of load i: byte offset of its chunk at k0 = 0 (0xFFFFFFFF if its row is out of
-    // range) and the chunk's k index inside the K step
-    static __device__ __forceinline__ void offsets(uint32_t (&vo)[NL], int (&kl)[NL], int64_t ld, int row0, int rows,
-                                                   int wave, int lane)
+    // The k index (inside the K step) of load i is that of load 0 plus a compile-time increment: zero for
+    // a K-contiguous tile (the swizzle repeats every 16 rows and LW loads cover a multiple of that), the
+    // number of k-rows LW wave-loads span for a K-strided one.
+    static_assert((LW * 64 / CPR) % 16 == 0, "K-contiguous swizzle must not depend on the load index");
+    static constexpr int K_INC = KCONTIG ? 0 : LW * 64 / (ROWS / 8);
+    static_assert(KCONTIG || (LW * 64) % (ROWS / 8) == 0, "K-strided loads must step whole k-rows");
+    // per-lane constants: byte offset of the chunk of load i at k0 = 0 (0xFFFFFFFF if its row is out of
+    // range) and the k index of load 0's chunk inside the K step
+    static __device__ __forceinline__ void offsets(uint32_t (&vo)[NL], int& kl0, int64_t ld, int row0, int rows, int lw,
+                                                   int lane)
     {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             int row, k;
-            chunk_of(i, wave, lane, row, k);
+            chunk_of(i, lw, lane, row, k);
             int grow = row0 + row;
             uint32_t off = KCONTIG ? (uint32_t)(((int64_t)grow * ld + k) * 2) : (uint32_t)(((int64_t)k * ld + grow) * 2);
             vo[i] = (grow < rows) ? off : 0xFFFFFFFFu;
-            kl[i] = k;
+            if (i == 0) kl0 = k;
         }
     }
     // Branch-free issue of one K step: chunks whose k index is at or beyond `krem` (the k left in the
     // segment; <= 0 once the schedule is exhausted) are pushed out of range and load zeros.
     static __device__ __forceinline__ void issue(char* tile, __amdgpu_buffer_rsrc_t rs, const uint32_t (&vo)[NL],
-                                                 const int (&kl)[NL], uint32_t soffset, int krem, int wave)
+                                                 int kl0, uint32_t soffset, int krem, int lw)
     {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
-            const uint32_t off = (kl[i] < krem) ? vo[i] : 0xFFFFFFFFu;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_ptr_t)(tile + (i * WAVES + wave) * 1024), 16, off,
+            const uint32_t off = (kl0 < krem - i * K_INC) ? vo[i] : 0xFFFFFFFFu;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_ptr_t)(tile + (i * LW + lw) * 1024), 16, off,
                                                      soffset, 0, 0);
         }
     }
@@ -176,14 +224,14 @@ __device__ __forceinline__ TileCoord map_tile(int wg, int tiles_m, int tiles_n, 
     return t;
 }
 
-// s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt in bits 3:0 and
-// 15:14, expcnt 6:4 and lgkmcnt 11:8 left at their maxima)
+// s_waitcnt with only one counter constrained (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt
+// 6:4, lgkmcnt 11:8; the others are left at their maxima)
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
 {
+    static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
     __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
 }
-
 template <int N>
 __device__ __forceinline__ void wait_lgkmcnt()
 {
@@ -196,14 +244,16 @@ __device__ __forceinline__ void wait_lgkmcnt()
 template <class T, bool A_KC, bool B_KC, int EPI, int TAG>
 __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
 {
-    // one launch may carry two independent problems of the same kind (e.g. base = x W^T and
-    // h = x A^T, or dA and dB): workgroups past count0 belong to the second one
+    // one launch may carry two independent problems of the same kind (e.g. dA and dB): workgroups
+    // past count0 belong to the second one
     const bool second = (int)blockIdx.x >= grp.count0;
     const GemmArgs& p = second ? grp.g[1] : grp.g[0];
     const int wg_id = (int)blockIdx.x - (second ? grp.count0 : 0);
-    constexpr int BM = T::BM, BN = T::BN, MT = T::MT, NT = T::NT;
+    constexpr int BM = T::BM, BN = T::BN, BK = T::BK, MT = T::MT, NT = T::NT;
+    constexpr int KSTEPS = BK / 16;  // MFMA k-steps per K step
     constexpr int FRAG_OPS = MT * (A_KC ? 1 : 2) + NT * (B_KC ? 1 : 2);  // LDS reads per k-step of 16
-    constexpr int LPT = T::NLA + T::NLB;  // load instructions per K step per lane
+    constexpr int LPT = T::NLA + T::NLB;  // load instructions per K step per loader lane
+    constexpr int STAGES = T::STAGES;
     __shared__ __attribute__((aligned(1024))) char smem[T::LDS_BYTES];
 
     const int tid = threadIdx.x;
@@ -254,13 +304,13 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
                 for (int e = 0; e < 16; ++e) acc[i][j][e] *= f;
     };
 
-    typedef OperandLoader<BM, T::NLA, T::WAVES, A_KC> LA;
-    typedef OperandLoader<BN, T::NLB, T::WAVES, B_KC> LB;
-    // Issue cursor: descriptors, per-lane offsets and the running scalar offsets of the segment the
-    // global -> LDS loads are currently walking.  It runs STAGES-1 steps ahead of the MFMAs and moves
-    // to the next segment (or to "exhausted": every further step loads zeros) on its own.
+    typedef OperandLoader<BM, BK, T::NLA, T::WAVES, A_KC> LA;
+    typedef OperandLoader<BN, BK, T::NLB, T::WAVES, B_KC> LB;
+    // Issue cursor: descriptors, per-lane offsets and the running scalar offsets
+    // of the segment the global -> LDS loads are currently walking.  It runs ahead of the MFMAs and
+    // moves to the next segment (or to "exhausted": every further step loads zeros) on its own.
     uint32_t voa[T::NLA], vob[T::NLB];
-    int kla[T::NLA], klb[T::NLB];
+    int kla = 0, klb = 0;
     __amdgpu_buffer_rsrc_t rsa, rsb;
     uint32_t so_a = 0, so_b = 0, so_step_a = 0, so_step_b = 0;  // scalar byte offsets and their per-step increments
     int krem = 0;        // k still to load in the cursor's segment (<= 0: exhausted)
@@ -289,19 +339,43 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
         char* st = smem + slot * T::STAGE_BYTES;
         LA::issue(st, rsa, voa, kla, so_a, krem, wave);
         LB::issue(st + T::A_BYTES, rsb, vob, klb, so_b, krem, wave);
-    };
-    auto advance = [&]() {
         so_a += so_step_a; so_b += so_step_b; krem -= BK;
         if (krem <= 0 && seg_cur == 0 && has_seg1) open_segment(1, 0, p.seg[1].K);
     };
-    auto frags = [&](bf16x8_t (&af)[MT], bf16x8_t (&bfr)[NT], int slot, int kk) {
-        const char* sa = smem + slot * T::STAGE_BYTES;
-        const char* sb = sa + T::A_BYTES;
+    // Per-lane LDS read offsets of the MFMA fragments, relative to the start of a ring slot.
+    // K-contiguous operand: one per k-step of 16; its 32-row blocks follow 32 rows apart, which the
+    // swizzle does not see, so they go into the instruction's immediate offset.  K-strided operand: one
+    // per 32-row block; its k-steps follow 16 k-rows apart, again an immediate.
+    typedef __attribute__((address_space(3))) const char* lds_cptr_t;
+    const uint32_t smem_lds = (uint32_t)(uintptr_t)(lds_cptr_t)smem;
+    uint32_t rda[4], rdb[4];
 #pragma unroll
-        for (int i = 0; i < MT; ++i) af[i] = load_frag<BM, A_KC>(sa, wm0 + i * 32, kk, lane);
-#pragma unroll
-        for (int j = 0; j < NT; ++j) bfr[j] = load_frag<BN, B_KC>(sb, wn0 + j * 32, kk, lane);
+    for (int q = 0; q < 4; ++q) {
+        rda[q] = A_KC ? frag_off<BM, BK, true>(wm0, q < KSTEPS ? q : 0, lane)
+                      : frag_off<BM, BK, false>(wm0 + (q < MT ? q : 0) * 32, 0, lane);
+        rdb[q] = T::A_BYTES + (B_KC ? frag_off<BN, BK, true>(wn0, q < KSTEPS ? q : 0, lane)
+                                    : frag_off<BN, BK, false>(wn0 + (q < NT ? q : 0) * 32, 0, lane));
+    }
+    static_assert(MT <= 4 && NT <= 4 && KSTEPS <= 4, "fragment offset tables hold four entries");
+    // fragments of k-step KK (compile time) of the K step held in the slot at LDS address `sbase`
+    auto frags = [&](auto kk_tag, bf16x8_t (&af)[MT], bf16x8_t (&bfr)[NT], uint32_t sbase) {
+        constexpr int KK = decltype(kk_tag)::value;
+        static_assert(KK < KSTEPS, "k-step outside the K step");
+        static_for<MT>([&](auto it) {
+            constexpr int i = decltype(it)::value;
+            if (A_KC) af[i] = lds_read_b128<i * 32 * BK * 2>(sbase + rda[KK]);
+            else af[i] = lds_read_tr<KK * 16 * BM * 2, 4 * BM * 2>(sbase + rda[i]);
+        });
+        static_for<NT>([&](auto jt) {
+            constexpr int j = decltype(jt)::value;
+            if (B_KC) bfr[j] = lds_read_b128<j * 32 * BK * 2>(sbase + rdb[KK]);
+            else bfr[j] = lds_read_tr<KK * 16 * BN * 2, 4 * BN * 2>(sbase + rdb[j]);
+        });
     };
+    typedef std::integral_constant<int, 0> K0;
+    typedef std::integral_constant<int, 1> K1;
+    typedef std::integral_constant<int, 2> K2;
+    typedef std::integral_constant<int, 3> K3;
     auto mma = [&](const bf16x8_t (&af)[MT], const bf16x8_t (&bfr)[NT], int kk) {
 #pragma unroll
         for (int i = 0; i < MT; ++i)
@@ -326,32 +400,30 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
             }
         }
     };
-    // Pipeline.  Ring slot u % 4 holds K step u; three steps are always in flight behind the one
-    // being multiplied (past the end of the schedule they are loads of zeros into free slots, which
-    // keeps the vmcnt bookkeeping uniform).  Per step: wait for its data, workgroup barrier (which
-    // also says every wave is done reading step u-1), read the first fragments of step u, then run
-    // the last MFMAs of step u-1 with the loads of step u+3 issued in their shadow.
+
     bf16x8_t a0[MT], b0[NT], a1[MT], b1[NT];
-    if (nsteps > 0) {
-#pragma unroll
-        for (int u = 0; u < STAGES - 1; ++u) { issue(u); advance(); }
-    }
-    if (T::WAVES == 8) {
-        // Ping-pong (8 waves = two per SIMD).  The waves form two groups of four, one wave of each
-        // group on every SIMD.  Time is cut into phases separated by workgroup barriers; in each phase
-        // one group runs the 16 MFMAs of a K step from registers while the other reads the fragments
-        // of its next step from LDS and issues its share of the global loads, then the roles swap:
+    if constexpr (T::WAVES == 8) {
+        // Ping-pong (two waves per SIMD).  The waves form two groups of four, one wave of each group
+        // on every SIMD.  Time is cut into phases separated by workgroup barriers; in each phase one
+        // group runs the 16 MFMAs of a K step (of 32) from registers while the other reads the
+        // fragments of its next step from LDS and issues its share of the global loads, then the roles
+        // swap:
         //     phase 2u   : group 0 multiplies step u   | group 1 fetches step u
         //     phase 2u+1 : group 0 fetches step u+1    | group 1 multiplies step u
-        // so the matrix pipe of every SIMD always has one wave feeding it and the memory
-        // instructions of the other wave issue in its shadow.
+        // so the matrix pipe of every SIMD always has one wave feeding it and the memory instructions
+        // of the other wave issue in its shadow.  Barriers are bare s_barriers with explicit counter
+        // waits (a fencing barrier would wait for every load in flight).
+        static_assert(KSTEPS == 2, "a ping-pong phase covers a K step of two MFMA k-steps");
+        if (nsteps > 0) {
+#pragma unroll
+            for (int u = 0; u < STAGES - 1; ++u) issue(u);
+        }
         const int grp_id = wave >> 2;
         auto fetch = [&](int u) {   // fragments of step u -> registers; refill the slot step u-1 used
-            const int slot = u % STAGES;
-            frags(a0, b0, slot, 0);
-            frags(a1, b1, slot, 1);
+            const uint32_t sbase = smem_lds + (u % STAGES) * T::STAGE_BYTES;
+            frags(K0{}, a0, b0, sbase);
+            frags(K1{}, a1, b1, sbase);
             issue((u + STAGES - 1) % STAGES);
-            advance();
         };
         auto compute = [&](int u) {
             wait_lgkmcnt<0>();
@@ -371,7 +443,7 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
             for (int u = 0; u < nsteps; ++u) {
                 __builtin_amdgcn_s_barrier();          // starts phase 2u
                 compute(u);
-                wait_vmcnt<(STAGES - 2) * LPT>();                 // own share of step u+1 landed
+                wait_vmcnt<(STAGES - 2) * LPT>();      // own share of step u+1 landed
                 __builtin_amdgcn_s_barrier();          // starts phase 2u+1: step u+1 complete, slot u free
                 if (u + 1 < nsteps) fetch(u + 1);
             }
@@ -387,32 +459,51 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
         }
         wait_vmcnt<0>();
     } else {
-    for (int u = 0; u < nsteps; ++u) {
-        const int slot = u % STAGES;
-        wait_vmcnt<(STAGES - 2) * LPT>();
-        // A bare s_barrier: __syncthreads() would also fence, i.e. wait for every load still in
-        // flight to the other ring slots.  What must be complete here is only this wave's share of
-        // step u (the vmcnt wait above) and its LDS reads of step u-1 (lgkmcnt).
+        static_assert(KSTEPS == 4, "the four-wave schedule is written for K steps of 64");
+        // Four waves, K steps of 64.  STAGES-1 K steps are in flight behind the one being
+        // multiplied.  Per K step (four k-steps of 16): wait for its data, workgroup barrier (which
+        // also says every wave is done reading the previous step), refill the buffer that step used,
+        // then alternate fragment reads and MFMAs with the fragments double buffered in registers; the
+        // last MFMAs of a step run after the next step's barrier and cover its first fragment reads.
+        if (nsteps > 0) {
+#pragma unroll
+            for (int u = 0; u < STAGES - 1; ++u) issue(u);
+        }
+        for (int u = 0; u < nsteps; ++u) {
+            const uint32_t sbase = smem_lds + (u % STAGES) * T::STAGE_BYTES;
+            wait_vmcnt<(STAGES - 2) * LPT>();
+            wait_lgkmcnt<0>();
+            __builtin_amdgcn_s_barrier();
+            frags(K0{}, a0, b0, sbase);
+            __builtin_amdgcn_sched_barrier(0);
+            issue((u + STAGES - 1) % STAGES);
+            if (u > 0) mma(a1, b1, 4 * (u - 1) + 3);     // its fragments were complete before the barrier
+            if (rescale && u == seg0_steps) rescale_acc();   // step u-1 was the last of segment 0
+            __builtin_amdgcn_sched_barrier(0);
+            frags(K1{}, a1, b1, sbase);
+            __builtin_amdgcn_sched_barrier(0);
+            wait_lgkmcnt<FRAG_OPS>();                    // a0/b0 landed; a1/b1 may still be in flight
+            __builtin_amdgcn_sched_barrier(0);
+            mma(a0, b0, 4 * u);
+            __builtin_amdgcn_sched_barrier(0);
+            frags(K2{}, a0, b0, sbase);
+            __builtin_amdgcn_sched_barrier(0);
+            wait_lgkmcnt<FRAG_OPS>();
+            __builtin_amdgcn_sched_barrier(0);
+            mma(a1, b1, 4 * u + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            frags(K3{}, a1, b1, sbase);
+            __builtin_amdgcn_sched_barrier(0);
+            wait_lgkmcnt<FRAG_OPS>();
+            __builtin_amdgcn_sched_barrier(0);
+            mma(a0, b0, 4 * u + 2);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        wait_vmcnt<0>();
         wait_lgkmcnt<0>();
-        __builtin_amdgcn_s_barrier();
-        frags(a0, b0, slot, 0);
         __builtin_amdgcn_sched_barrier(0);
-        issue((u + STAGES - 1) % STAGES);
-        if (u > 0) mma(a1, b1, 2 * (u - 1) + 1);   // its fragments were complete before the barrier
-        if (rescale && u == seg0_steps) rescale_acc();   // step u-1 was the last of segment 0
-        __builtin_amdgcn_sched_barrier(0);
-        frags(a1, b1, slot, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        wait_lgkmcnt<FRAG_OPS>();                  // a0/b0 landed; a1/b1 may still be in flight
-        __builtin_amdgcn_sched_barrier(0);
-        mma(a0, b0, 2 * u);
-        __builtin_amdgcn_sched_barrier(0);
-        advance();
-    }
-    wait_vmcnt<0>();
-    wait_lgkmcnt<0>();
-    __builtin_amdgcn_sched_barrier(0);
-    if (nsteps > 0) mma(a1, b1, 2 * (nsteps - 1) + 1);
+        if (nsteps > 0) mma(a1, b1, 4 * (nsteps - 1) + 3);
+        if (rescale && nsteps == seg0_steps && nsteps > 0) rescale_acc();
     }
     __syncthreads();
 
@@ -553,20 +644,25 @@ bool use_big(const GemmArgs& a)
 hipError_t dispatch(const GemmArgs& a, const GemmArgs* b, hipStream_t stream)
 {
     const bool big = use_big(a);
+    // at most one 128x128-tile workgroup per CU: give it the deep ring
+    const bool deep = !big && (grid_of<TileMed>(a) + (b ? grid_of<TileMed>(*b) : 0)) <= 256;
+#define DORA_GEMM_MED(AKC, BKC, E) \
+    (deep ? launch_one<TileMedDeep, AKC, BKC, E>(a, b, stream) : launch_one<TileMed, AKC, BKC, E>(a, b, stream))
 #define DORA_GEMM_CASE(AKC, BKC, E)                                                     \
     if (a.a_kcontig == (AKC) && a.b_kcontig == (BKC) && a.epilogue == (E))              \
-        return big ? launch_one<TileBig, AKC, BKC, E>(a, b, stream) : launch_one<TileMed, AKC, BKC, E>(a, b, stream);
+        return big ? launch_one<TileBig, AKC, BKC, E>(a, b, stream) : DORA_GEMM_MED(AKC, BKC, E);
     DORA_GEMM_CASE(true, true, EPI_STORE_BF16)
     DORA_GEMM_CASE(true, false, EPI_STORE_BF16)
     DORA_GEMM_CASE(true, true, EPI_COMPOSE)
 #undef DORA_GEMM_CASE
 #define DORA_GEMM_CASE_MED(AKC, BKC, E)                                                 \
     if (a.a_kcontig == (AKC) && a.b_kcontig == (BKC) && a.epilogue == (E))              \
-        return launch_one<TileMed, AKC, BKC, E>(a, b, stream);
+        return DORA_GEMM_MED(AKC, BKC, E);
     DORA_GEMM_CASE_MED(true, true, EPI_STORE_F32)
     DORA_GEMM_CASE_MED(true, true, EPI_ROWDOT)
     DORA_GEMM_CASE_MED(false, false, EPI_STORE_F32)
 #undef DORA_GEMM_CASE_MED
+#undef DORA_GEMM_MED
     return hipErrorInvalidValue;
 }
 
