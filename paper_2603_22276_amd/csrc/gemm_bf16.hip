@@ -44,8 +44,15 @@ struct Tile {
     static constexpr int NLA = BM * CPR / THREADS;  // 16-byte loads per lane per K step, M side
     static constexpr int NLB = BN * CPR / THREADS;
     static constexpr int EPI_BYTES_PER_WAVE = 32 * (WN * 4 + 16);
-    static constexpr int LDS_BYTES = (STAGES * STAGE_BYTES > WAVES * EPI_BYTES_PER_WAVE) ? STAGES * STAGE_BYTES
-                                                                                        : WAVES * EPI_BYTES_PER_WAVE;
+    // Four waves of 128 x 128 each: the M-side operand gets a ring one deeper than STAGES and the two
+    // rings lie one after the other; otherwise slot s holds the M-side tile followed by the N-side tile.
+    static constexpr bool SPLIT_RING = (WAVES == 4) && (MT * NT >= 16);
+    static constexpr int A_STAGES = SPLIT_RING ? STAGES + 1 : STAGES, B_STAGES = STAGES;
+    static constexpr int RING_BYTES = A_STAGES * A_BYTES + B_STAGES * B_BYTES;
+    static constexpr int LDS_BYTES = (RING_BYTES > WAVES * EPI_BYTES_PER_WAVE) ? RING_BYTES : WAVES * EPI_BYTES_PER_WAVE;
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS of a gfx950 CU");
+    static constexpr int a_slot_off(int s) { return SPLIT_RING ? s * A_BYTES : s * STAGE_BYTES; }
+    static constexpr int b_slot_off(int s) { return SPLIT_RING ? A_STAGES * A_BYTES + s * B_BYTES : s * STAGE_BYTES + A_BYTES; }
     static_assert(BK == 32 || BK == 64, "LDS layouts exist for K steps of 32 and 64");
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
     static_assert(WAVES == 4 || WAVES == 8, "schedules exist for 4 and 8 waves");
@@ -53,6 +60,7 @@ struct Tile {
 };
 
 typedef Tile<256, 256, 2, 4, 32, 4> TileBig;      // 512 threads, 4 x 32 KB of LDS, 128 accumulator registers per lane
+typedef Tile<256, 256, 2, 2, 64, 2> TileBig4;     // 256 threads, (3 + 2) x 32 KB of LDS, 256 accumulator registers (AGPRs) per lane
 typedef Tile<128, 128, 2, 2, 64, 2> TileMed;      // 256 threads, 2 x 32 KB of LDS, two workgroups fit a CU
 typedef Tile<128, 128, 2, 2, 64, 4> TileMedDeep;  // the same with a ring of four, for launches of at most one workgroup per CU
 
@@ -187,16 +195,49 @@ struct OperandLoader {
     }
     // Branch-free issue of one K step: chunks whose k index is at or beyond `krem` (the k left in the
     // segment; <= 0 once the schedule is exhausted) are pushed out of range and load zeros.
+    template <int I>
+    static __device__ __forceinline__ void issue_one(char* tile, __amdgpu_buffer_rsrc_t rs, const uint32_t (&vo)[NL],
+                                                     int kl0, uint32_t soffset, int krem, int lw)
+    {
+        static_assert(I >= 0 && I < NL, "load index");
+        const uint32_t off = (kl0 < krem - I * K_INC) ? vo[I] : 0xFFFFFFFFu;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_ptr_t)(tile + (I * LW + lw) * 1024), 16, off, soffset, 0,
+                                                 0);
+    }
     static __device__ __forceinline__ void issue(char* tile, __amdgpu_buffer_rsrc_t rs, const uint32_t (&vo)[NL],
                                                  int kl0, uint32_t soffset, int krem, int lw)
     {
-#pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            const uint32_t off = (kl0 < krem - i * K_INC) ? vo[i] : 0xFFFFFFFFu;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_ptr_t)(tile + (i * LW + lw) * 1024), 16, off,
-                                                     soffset, 0, 0);
-        }
+        static_for<NL>([&](auto it) { issue_one<decltype(it)::value>(tile, rs, vo, kl0, soffset, krem, lw); });
     }
+};
+
+// Issue cursor of one operand: descriptor, per-lane offsets and the running scalar offset of the
+// segment its global -> LDS loads are walking.  It runs ahead of the MFMAs.
+template <class L, int NL, int BK, bool KCONTIG>
+struct Cursor {
+    uint32_t vo[NL];
+    int kl0;
+    __amdgpu_buffer_rsrc_t rs;
+    uint32_t so, so_step;   // scalar byte offset of the next K step and its increment
+    int krem;               // k still to load in the segment (<= 0: exhausted, every further load brings zeros)
+    int seg;
+    __device__ __forceinline__ void open(int sidx, const bf16_t* base, int64_t ld, int K, int row0, int rows, int k_first,
+                                         int k_last, int wave, int lane)
+    {
+        rs = L::make_rsrc(base, ld, rows, K);
+        L::offsets(vo, kl0, ld, row0, rows, wave, lane);
+        so_step = KCONTIG ? (uint32_t)(BK * 2) : (uint32_t)(BK * ld * 2);
+        so = KCONTIG ? (uint32_t)(k_first * 2) : (uint32_t)((int64_t)k_first * ld * 2);
+        krem = (k_last < K ? k_last : K) - k_first;
+        seg = sidx;
+    }
+    template <int I>
+    __device__ __forceinline__ void issue_one(char* tile, int wave) const
+    {
+        L::template issue_one<I>(tile, rs, vo, kl0, so, krem, wave);
+    }
+    __device__ __forceinline__ void issue_all(char* tile, int wave) const { L::issue(tile, rs, vo, kl0, so, krem, wave); }
+    __device__ __forceinline__ void step() { so += so_step; krem -= BK; }
 };
 
 struct TileCoord { int tm, tn, z; };
@@ -293,7 +334,8 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
     // K steps of segment 0 inside this workgroup's range; when they are done the accumulators may be
     // rescaled once (used to apply s to the low-rank segment of the K-concatenated forward)
     const int seg0_steps = (t_end < kt0_total ? t_end : kt0_total) - t_begin;
-    const bool rescale = (p.seg0_scale != 0.f) && (p.nseg > 1);
+    // only the compose epilogue (K-concatenated forward) uses the rescale; elsewhere the code is compiled out
+    const bool rescale = (EPI == EPI_COMPOSE) && (p.seg0_scale != 0.f) && (p.nseg > 1);
     auto rescale_acc = [&]() {
         const float f = p.seg0_scale;
 #pragma unroll
@@ -306,43 +348,38 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
 
     typedef OperandLoader<BM, BK, T::NLA, T::WAVES, A_KC> LA;
     typedef OperandLoader<BN, BK, T::NLB, T::WAVES, B_KC> LB;
-    // Issue cursor: descriptors, per-lane offsets and the running scalar offsets
-    // of the segment the global -> LDS loads are currently walking.  It runs ahead of the MFMAs and
-    // moves to the next segment (or to "exhausted": every further step loads zeros) on its own.
-    uint32_t voa[T::NLA], vob[T::NLB];
-    int kla = 0, klb = 0;
-    __amdgpu_buffer_rsrc_t rsa, rsb;
-    uint32_t so_a = 0, so_b = 0, so_step_a = 0, so_step_b = 0;  // scalar byte offsets and their per-step increments
-    int krem = 0;        // k still to load in the cursor's segment (<= 0: exhausted)
-    int seg_cur = 0;
-    auto open_segment = [&](int sidx, int k_first, int k_last) {
-        const GemmSeg& sg = p.seg[sidx];
-        rsa = LA::make_rsrc(sg.a, sg.lda, p.M, sg.K);
-        rsb = LB::make_rsrc(sg.b, sg.ldb, p.N, sg.K);
-        LA::offsets(voa, kla, sg.lda, m0, p.M, wave, lane);
-        LB::offsets(vob, klb, sg.ldb, n0, p.N, wave, lane);
-        so_step_a = A_KC ? (uint32_t)(BK * 2) : (uint32_t)(BK * sg.lda * 2);
-        so_step_b = B_KC ? (uint32_t)(BK * 2) : (uint32_t)(BK * sg.ldb * 2);
-        so_a = A_KC ? (uint32_t)(k_first * 2) : (uint32_t)((int64_t)k_first * sg.lda * 2);
-        so_b = B_KC ? (uint32_t)(k_first * 2) : (uint32_t)((int64_t)k_first * sg.ldb * 2);
-        krem = (k_last < sg.K ? k_last : sg.K) - k_first;
-        seg_cur = sidx;
-    };
-    // segment 0 covers K steps [t_begin, min(t_end, kt0_total)); segment 1 (never split) the rest
+    // One cursor per operand; each moves to the next segment (or to "exhausted") on its own.
+    // Segment 0 covers K steps [t_begin, min(t_end, kt0_total)); segment 1 (never split) the rest.
+    Cursor<LA, T::NLA, BK, A_KC> ca;
+    Cursor<LB, T::NLB, BK, B_KC> cb;
     const bool has_seg1 = (p.nseg > 1) && (t_end > kt0_total);
-    {
-        const int e0 = t_end < kt0_total ? t_end : kt0_total;
-        open_segment(0, t_begin * BK, e0 * BK);
-        if (krem <= 0 && has_seg1) open_segment(1, 0, p.seg[1].K);
-    }
-    auto issue = [&](int slot) {
-        char* st = smem + slot * T::STAGE_BYTES;
-        LA::issue(st, rsa, voa, kla, so_a, krem, wave);
-        LB::issue(st + T::A_BYTES, rsb, vob, klb, so_b, krem, wave);
-        so_a += so_step_a; so_b += so_step_b; krem -= BK;
-        if (krem <= 0 && seg_cur == 0 && has_seg1) open_segment(1, 0, p.seg[1].K);
+    const int seg0_k0 = t_begin * BK, seg0_k1 = (t_end < kt0_total ? t_end : kt0_total) * BK;
+    auto open_a = [&](int sidx) {
+        const GemmSeg& sg = p.seg[sidx];
+        ca.open(sidx, sg.a, sg.lda, sg.K, m0, p.M, sidx ? 0 : seg0_k0, sidx ? sg.K : seg0_k1, wave, lane);
     };
-    // Per-lane LDS read offsets of the MFMA fragments, relative to the start of a ring slot.
+    auto open_b = [&](int sidx) {
+        const GemmSeg& sg = p.seg[sidx];
+        cb.open(sidx, sg.b, sg.ldb, sg.K, n0, p.N, sidx ? 0 : seg0_k0, sidx ? sg.K : seg0_k1, wave, lane);
+    };
+    open_a(0);
+    open_b(0);
+    if (ca.krem <= 0 && has_seg1) { open_a(1); open_b(1); }
+    auto advance_a = [&]() {
+        ca.step();
+        if (ca.krem <= 0 && ca.seg == 0 && has_seg1) open_a(1);
+    };
+    auto advance_b = [&]() {
+        cb.step();
+        if (cb.krem <= 0 && cb.seg == 0 && has_seg1) open_b(1);
+    };
+    auto issue = [&](int slot) {   // every load of the next K step of both operands
+        ca.issue_all(smem + T::a_slot_off(slot), wave);
+        cb.issue_all(smem + T::b_slot_off(slot), wave);
+        advance_a();
+        advance_b();
+    };
+    // Per-lane LDS read offsets of the MFMA fragments, relative to the start of the operand's tile.
     // K-contiguous operand: one per k-step of 16; its 32-row blocks follow 32 rows apart, which the
     // swizzle does not see, so they go into the instruction's immediate offset.  K-strided operand: one
     // per 32-row block; its k-steps follow 16 k-rows apart, again an immediate.
@@ -353,24 +390,27 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
     for (int q = 0; q < 4; ++q) {
         rda[q] = A_KC ? frag_off<BM, BK, true>(wm0, q < KSTEPS ? q : 0, lane)
                       : frag_off<BM, BK, false>(wm0 + (q < MT ? q : 0) * 32, 0, lane);
-        rdb[q] = T::A_BYTES + (B_KC ? frag_off<BN, BK, true>(wn0, q < KSTEPS ? q : 0, lane)
-                                    : frag_off<BN, BK, false>(wn0 + (q < NT ? q : 0) * 32, 0, lane));
+        rdb[q] = B_KC ? frag_off<BN, BK, true>(wn0, q < KSTEPS ? q : 0, lane)
+                      : frag_off<BN, BK, false>(wn0 + (q < NT ? q : 0) * 32, 0, lane);
     }
     static_assert(MT <= 4 && NT <= 4 && KSTEPS <= 4, "fragment offset tables hold four entries");
-    // fragments of k-step KK (compile time) of the K step held in the slot at LDS address `sbase`
-    auto frags = [&](auto kk_tag, bf16x8_t (&af)[MT], bf16x8_t (&bfr)[NT], uint32_t sbase) {
-        constexpr int KK = decltype(kk_tag)::value;
+    // fragment f (M side first) of k-step KK (both compile time) of the tiles at LDS addresses sa, sb
+    auto read_frag = [&](auto kk_tag, auto f_tag, bf16x8_t (&af)[MT], bf16x8_t (&bfr)[NT], uint32_t sa, uint32_t sb) {
+        constexpr int KK = decltype(kk_tag)::value, f = decltype(f_tag)::value;
         static_assert(KK < KSTEPS, "k-step outside the K step");
-        static_for<MT>([&](auto it) {
-            constexpr int i = decltype(it)::value;
-            if (A_KC) af[i] = lds_read_b128<i * 32 * BK * 2>(sbase + rda[KK]);
-            else af[i] = lds_read_tr<KK * 16 * BM * 2, 4 * BM * 2>(sbase + rda[i]);
-        });
-        static_for<NT>([&](auto jt) {
-            constexpr int j = decltype(jt)::value;
-            if (B_KC) bfr[j] = lds_read_b128<j * 32 * BK * 2>(sbase + rdb[KK]);
-            else bfr[j] = lds_read_tr<KK * 16 * BN * 2, 4 * BN * 2>(sbase + rdb[j]);
-        });
+        if constexpr (f < MT) {
+            if (A_KC) af[f] = lds_read_b128<f * 32 * BK * 2>(sa + rda[KK]);
+            else af[f] = lds_read_tr<KK * 16 * BM * 2, 4 * BM * 2>(sa + rda[f]);
+        } else {
+            constexpr int j = f - MT;
+            if (B_KC) bfr[j] = lds_read_b128<j * 32 * BK * 2>(sb + rdb[KK]);
+            else bfr[j] = lds_read_tr<KK * 16 * BN * 2, 4 * BN * 2>(sb + rdb[j]);
+        }
+    };
+    // all fragments of k-step KK of ring slot `slot`
+    auto frags = [&](auto kk_tag, bf16x8_t (&af)[MT], bf16x8_t (&bfr)[NT], int slot) {
+        const uint32_t sa = smem_lds + T::a_slot_off(slot), sb = smem_lds + T::b_slot_off(slot);
+        static_for<MT + NT>([&](auto ft) { read_frag(kk_tag, ft, af, bfr, sa, sb); });
     };
     typedef std::integral_constant<int, 0> K0;
     typedef std::integral_constant<int, 1> K1;
@@ -420,9 +460,8 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
         }
         const int grp_id = wave >> 2;
         auto fetch = [&](int u) {   // fragments of step u -> registers; refill the slot step u-1 used
-            const uint32_t sbase = smem_lds + (u % STAGES) * T::STAGE_BYTES;
-            frags(K0{}, a0, b0, sbase);
-            frags(K1{}, a1, b1, sbase);
+            frags(K0{}, a0, b0, u % STAGES);
+            frags(K1{}, a1, b1, u % STAGES);
             issue((u + STAGES - 1) % STAGES);
         };
         auto compute = [&](int u) {
@@ -458,10 +497,110 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
             }
         }
         wait_vmcnt<0>();
+    } else if constexpr (T::SPLIT_RING) {
+        // Four waves, one per SIMD, each owning 128 x 128 of the tile (accumulators in the AGPR half of
+        // the register file).  This shape needs the fewest LDS bytes per MFMA (eight fragment reads feed
+        // sixteen MFMAs), which matters because the LDS path of a SIMD moves a 16-byte-per-lane read in
+        // about the time of one MFMA.  With a single wave per SIMD nothing else hides the issue of memory
+        // instructions, so they are interleaved with the MFMAs by hand.  A "burst" runs the sixteen
+        // MFMAs of one k-step from one fragment set; behind each of the first eight, one fragment of the
+        // next k-step is read into the other set; behind the others, a quarter of a K step's global
+        // loads is issued.  (All of a K step's loads behind one barrier would block the waves at the
+        // address unit, which takes 16 cycles per load instruction.)  One workgroup barrier per K step.
+        //
+        // LDS holds three M-side tiles and two N-side tiles.  With barrier(u) = the barrier at which all
+        // reads of K step u are done, the loads of a step are issued as
+        //     N side, step u+2:  first half behind barrier(u), second half in the burst after it,
+        //     M side, step u+3:  the two bursts after that,
+        // N side before M side, so that waiting for all but the last M-side step's loads means the N-side
+        // ones have landed (loads complete in order).  The N-side loads have most of a K step to land,
+        // the M-side ones that plus a whole step.
+        constexpr int NM = MT * NT, NF = MT + NT;
+        constexpr int HA = T::NLA / 2, HB = T::NLB / 2;
+        static_assert(KSTEPS == 4 && NF <= NM && STAGES == 2, "burst schedule assumptions");
+        // MFMAs of the k-step held in (xa, xb); fragments of k-step KK of (sa, sb) -> (na, nb); loads
+        // [D0, D0 + DN) of the M side (SIDE 0) or N side (SIDE 1) into `tile`
+        auto burst = [&](auto kk_tag, auto side_tag, auto d0_tag, auto dn_tag, const bf16x8_t (&xa)[MT],
+                         const bf16x8_t (&xb)[NT], bf16x8_t (&na)[MT], bf16x8_t (&nb)[NT], uint32_t sa, uint32_t sb,
+                         char* tile) {
+            constexpr int SIDE = decltype(side_tag)::value, D0 = decltype(d0_tag)::value, DN = decltype(dn_tag)::value;
+            static_for<NM>([&](auto nt) {
+                constexpr int n = decltype(nt)::value;
+                constexpr int i = n / NT, j = n % NT;
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xb[j], xa[i], acc[i][j], 0, 0, 0);
+                if constexpr (n < NF) {
+                    read_frag(kk_tag, nt, na, nb, sa, sb);
+                } else {
+                    // the DN loads spread evenly over the MFMAs that have no fragment read behind them
+                    constexpr int lo = ((n - NF) * DN + (NM - NF) - 1) / (NM - NF);
+                    constexpr int hi = ((n + 1 - NF) * DN + (NM - NF) - 1) / (NM - NF);
+                    static_for<hi - lo>([&](auto dt) {
+                        constexpr int t = D0 + lo + decltype(dt)::value;
+                        if constexpr (SIDE == 0) {
+                            ca.template issue_one<t>(tile, wave);
+                            if constexpr (t == T::NLA - 1) advance_a();
+                        } else {
+                            cb.template issue_one<t>(tile, wave);
+                            if constexpr (t == T::NLB - 1) advance_b();
+                        }
+                    });
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        };
+        typedef std::integral_constant<int, 0> SideA;
+        typedef std::integral_constant<int, 1> SideB;
+        typedef std::integral_constant<int, 0> I0;
+        typedef std::integral_constant<int, HA> IHA;
+        typedef std::integral_constant<int, T::NLA - HA> IRA;
+        typedef std::integral_constant<int, HB> IHB;
+        typedef std::integral_constant<int, T::NLB - HB> IRB;
+        // before the loop: M side steps 0 and 1, N side step 0 and the first half of step 1
+        ca.issue_all(smem + T::a_slot_off(0), wave);
+        advance_a();
+        cb.issue_all(smem + T::b_slot_off(0), wave);
+        advance_b();
+        ca.issue_all(smem + T::a_slot_off(1), wave);
+        advance_a();
+        static_for<HB>([&](auto t) { cb.template issue_one<decltype(t)::value>(smem + T::b_slot_off(1), wave); });
+        wait_vmcnt<T::NLA + HB>();                     // own share of step 0 landed
+        __builtin_amdgcn_s_barrier();                  // all of step 0 landed
+        frags(K0{}, a0, b0, 0);
+        int sa_cur = 0, sa_nxt = 1, sa_fill = 2;       // M-side slots of steps u, u+1, u+2 (mod 3)
+        for (int u = 0; u < nsteps; ++u) {
+            const uint32_t sa = smem_lds + T::a_slot_off(sa_cur), sb = smem_lds + T::b_slot_off(u & 1);
+            const uint32_t sa1 = smem_lds + T::a_slot_off(sa_nxt), sb1 = smem_lds + T::b_slot_off((u + 1) & 1);
+            wait_lgkmcnt<0>();
+            __builtin_amdgcn_sched_barrier(0);
+            // step u, k-step 0; rest of the N side of step u+1
+            burst(K1{}, SideB{}, IHB{}, IRB{}, a0, b0, a1, b1, sa, sb, smem + T::b_slot_off((u + 1) & 1));
+            wait_lgkmcnt<0>();
+            __builtin_amdgcn_sched_barrier(0);
+            // k-step 1; M side of step u+2, first half
+            burst(K2{}, SideA{}, I0{}, IHA{}, a1, b1, a0, b0, sa, sb, smem + T::a_slot_off(sa_fill));
+            wait_lgkmcnt<0>();
+            __builtin_amdgcn_sched_barrier(0);
+            // k-step 2; M side of step u+2, second half
+            burst(K3{}, SideA{}, IHA{}, IRA{}, a0, b0, a1, b1, sa, sb, smem + T::a_slot_off(sa_fill));
+            // Everything but the M side of step u+2 has landed, i.e. all of step u+1 (own share); own
+            // reads of step u are done.  After the barrier step u+1 is visible to all and the slots of
+            // step u may be refilled.
+            __builtin_amdgcn_sched_barrier(0);
+            wait_vmcnt<T::NLA>();
+            wait_lgkmcnt<0>();
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);          // no MFMA may move above the waits
+            // k-step 3 and the first fragments of step u+1; N side of step u+2, first half
+            burst(K0{}, SideB{}, I0{}, IHB{}, a1, b1, a0, b0, sa1, sb1, smem + T::b_slot_off(u & 1));
+            if (rescale && u == seg0_steps - 1) rescale_acc();
+            const int t = sa_cur;
+            sa_cur = sa_nxt; sa_nxt = sa_fill; sa_fill = t;
+        }
+        wait_vmcnt<0>();
+        wait_lgkmcnt<0>();
     } else {
-        static_assert(KSTEPS == 4, "the four-wave schedule is written for K steps of 64");
-        // Four waves, K steps of 64.  STAGES-1 K steps are in flight behind the one being
-        // multiplied.  Per K step (four k-steps of 16): wait for its data, workgroup barrier (which
+        // Four waves.  STAGES-1 K steps are in flight behind the one being
+        // multiplied.  Per K step (two or four k-steps of 16): wait for its data, workgroup barrier (which
         // also says every wave is done reading the previous step), refill the buffer that step used,
         // then alternate fragment reads and MFMAs with the fragments double buffered in registers; the
         // last MFMAs of a step run after the next step's barrier and cover its first fragment reads.
@@ -470,39 +609,40 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
             for (int u = 0; u < STAGES - 1; ++u) issue(u);
         }
         for (int u = 0; u < nsteps; ++u) {
-            const uint32_t sbase = smem_lds + (u % STAGES) * T::STAGE_BYTES;
+            const int slot = u % STAGES;
+            __builtin_amdgcn_sched_barrier(0);
             wait_vmcnt<(STAGES - 2) * LPT>();
             wait_lgkmcnt<0>();
             __builtin_amdgcn_s_barrier();
-            frags(K0{}, a0, b0, sbase);
+            __builtin_amdgcn_sched_barrier(0);          // no MFMA may move above the waits
+            frags(K0{}, a0, b0, slot);
             __builtin_amdgcn_sched_barrier(0);
             issue((u + STAGES - 1) % STAGES);
-            if (u > 0) mma(a1, b1, 4 * (u - 1) + 3);     // its fragments were complete before the barrier
+            if (u > 0) mma(a1, b1, KSTEPS * u - 1);      // its fragments were complete before the barrier
             if (rescale && u == seg0_steps) rescale_acc();   // step u-1 was the last of segment 0
             __builtin_amdgcn_sched_barrier(0);
-            frags(K1{}, a1, b1, sbase);
-            __builtin_amdgcn_sched_barrier(0);
-            wait_lgkmcnt<FRAG_OPS>();                    // a0/b0 landed; a1/b1 may still be in flight
-            __builtin_amdgcn_sched_barrier(0);
-            mma(a0, b0, 4 * u);
-            __builtin_amdgcn_sched_barrier(0);
-            frags(K2{}, a0, b0, sbase);
-            __builtin_amdgcn_sched_barrier(0);
-            wait_lgkmcnt<FRAG_OPS>();
-            __builtin_amdgcn_sched_barrier(0);
-            mma(a1, b1, 4 * u + 1);
-            __builtin_amdgcn_sched_barrier(0);
-            frags(K3{}, a1, b1, sbase);
-            __builtin_amdgcn_sched_barrier(0);
-            wait_lgkmcnt<FRAG_OPS>();
-            __builtin_amdgcn_sched_barrier(0);
-            mma(a0, b0, 4 * u + 2);
-            __builtin_amdgcn_sched_barrier(0);
+            static_for<KSTEPS / 2>([&](auto qt) {
+                constexpr int q = decltype(qt)::value;
+                frags(std::integral_constant<int, 2 * q + 1>{}, a1, b1, slot);
+                __builtin_amdgcn_sched_barrier(0);
+                wait_lgkmcnt<FRAG_OPS>();                // a0/b0 landed; a1/b1 may still be in flight
+                __builtin_amdgcn_sched_barrier(0);
+                mma(a0, b0, KSTEPS * u + 2 * q);
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (2 * q + 2 < KSTEPS) {
+                    frags(std::integral_constant<int, 2 * q + 2>{}, a0, b0, slot);
+                    __builtin_amdgcn_sched_barrier(0);
+                    wait_lgkmcnt<FRAG_OPS>();
+                    __builtin_amdgcn_sched_barrier(0);
+                    mma(a1, b1, KSTEPS * u + 2 * q + 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            });
         }
         wait_vmcnt<0>();
         wait_lgkmcnt<0>();
         __builtin_amdgcn_sched_barrier(0);
-        if (nsteps > 0) mma(a1, b1, 4 * (nsteps - 1) + 3);
+        if (nsteps > 0) mma(a1, b1, KSTEPS * nsteps - 1);
         if (rescale && nsteps == seg0_steps && nsteps > 0) rescale_acc();
     }
     __syncthreads();
@@ -634,6 +774,11 @@ hipError_t launch_one(const GemmArgs& a, const GemmArgs* b, hipStream_t stream)
     return hipGetLastError();
 }
 
+// 256 x 256 tile per epilogue: the compose epilogue rescales the accumulators between its two K
+// segments, which does not fit beside 256 accumulator registers per lane, so it keeps the 8-wave tile.
+template <int EPI> struct BigTileFor { typedef TileBig4 type; };
+template <> struct BigTileFor<EPI_COMPOSE> { typedef TileBig type; };
+
 bool use_big(const GemmArgs& a)
 {
     // the large tile pays off once it still yields a few tiles per CU
@@ -650,7 +795,7 @@ hipError_t dispatch(const GemmArgs& a, const GemmArgs* b, hipStream_t stream)
     (deep ? launch_one<TileMedDeep, AKC, BKC, E>(a, b, stream) : launch_one<TileMed, AKC, BKC, E>(a, b, stream))
 #define DORA_GEMM_CASE(AKC, BKC, E)                                                     \
     if (a.a_kcontig == (AKC) && a.b_kcontig == (BKC) && a.epilogue == (E))              \
-        return big ? launch_one<TileBig, AKC, BKC, E>(a, b, stream) : DORA_GEMM_MED(AKC, BKC, E);
+        return big ? launch_one<typename BigTileFor<E>::type, AKC, BKC, E>(a, b, stream) : DORA_GEMM_MED(AKC, BKC, E);
     DORA_GEMM_CASE(true, true, EPI_STORE_BF16)
     DORA_GEMM_CASE(true, false, EPI_STORE_BF16)
     DORA_GEMM_CASE(true, true, EPI_COMPOSE)
