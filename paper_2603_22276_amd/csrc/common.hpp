@@ -75,10 +75,10 @@ struct GemmArgs {
     int64_t ldc;
     int ksplit;                // split of segment 0's K range (nseg must be 1 when > 1)
     int tag;                   // 0 or 1: selects a differently named (otherwise identical) kernel instance
-    float seg0_scale;          // accumulators are multiplied by this once segment 0 is done (0 = off)
-    // EPI_COMPOSE only
-    const float* colscale;     // [N] fp32
-    void* c2;                  // second output [M, ldc] bf16 (unscaled accumulator) or nullptr
+    const float* colscale;     // EPI_COMPOSE: [N] fp32
+    void* c2;                  // second output [M, ldc] bf16 or nullptr: the unscaled accumulator (compose epilogue),
+                               // alpha2 * accumulator (bf16 store epilogue)
+    float alpha2;
     // EPI_ROWDOT only
     const bf16_t* rowdot;      // R [M, ld_rowdot] bf16
     int64_t ld_rowdot;

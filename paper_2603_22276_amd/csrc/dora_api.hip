@@ -249,9 +249,10 @@ dora_status norm_impl(const dora_desc* d, const void* W, const void* A, const vo
 struct FwdPlan {
     NormPlan norm;
     float *c, *g, *gm1;
-    void *h, *lora;
+    void *h, *lora, *hs;
 };
-void plan_fwd(const dora_desc* d, Bump& b, FwdPlan& p, bool need_norm, bool need_h, bool need_lora)
+void plan_fwd(const dora_desc* d, Bump& b, FwdPlan& p, bool need_norm, bool need_h, bool need_lora,
+              bool need_hs = false)
 {
     memset(&p, 0, sizeof(p));
     if (need_norm) plan_norm(d, b, p.norm);
@@ -260,6 +261,7 @@ void plan_fwd(const dora_desc* d, Bump& b, FwdPlan& p, bool need_norm, bool need
     p.gm1 = b.take<float>((size_t)d->d_out);
     if (need_h) p.h = b.take_bytes((size_t)d->tokens * d->r * esize(d->dtype));
     if (need_lora) p.lora = b.take_bytes((size_t)d->tokens * d->d_out * esize(d->dtype));
+    if (need_hs) p.hs = b.take_bytes((size_t)d->tokens * d->r * esize(d->dtype));
 }
 
 struct BwdPlan {
@@ -338,7 +340,7 @@ size_t dora_workspace_bytes(const dora_desc* desc, int phase)
     Bump b(nullptr);
     switch (phase) {
         case DORA_PHASE_NORM: { NormPlan n; plan_norm(desc, b, n); break; }
-        case DORA_PHASE_FORWARD: { FwdPlan p; plan_fwd(desc, b, p, true, true, true); break; }
+        case DORA_PHASE_FORWARD: { FwdPlan p; plan_fwd(desc, b, p, true, true, true, true); break; }
         case DORA_PHASE_BACKWARD: { BwdPlan p; plan_bwd(desc, b, p, false, false, false); break; }
         case DORA_PHASE_BACKWARD_RECOMPUTE: { BwdPlan p; plan_bwd(desc, b, p, true, true, true); break; }
         default: return 0;
@@ -467,10 +469,10 @@ dora_status dora_forward_fused(const dora_desc* desc, const void* x, const void*
     const bool need_norm = (w_norm == nullptr);
     Bump sizing(nullptr);
     FwdPlan p;
-    plan_fwd(desc, sizing, p, need_norm, saved_h == nullptr, false);
+    plan_fwd(desc, sizing, p, need_norm, saved_h == nullptr, false, true);
     if ((st = check_ws(ws, ws_bytes, sizing.off)) != DORA_OK) return st;
     Bump b(ws);
-    plan_fwd(desc, b, p, need_norm, saved_h == nullptr, false);
+    plan_fwd(desc, b, p, need_norm, saved_h == nullptr, false, true);
     hipStream_t s = (hipStream_t)stream;
     const int T = (int)desc->tokens, d_out = (int)desc->d_out, d_in = (int)desc->d_in, r = (int)desc->r;
 
@@ -484,13 +486,17 @@ dora_status dora_forward_fused(const dora_desc* desc, const void* x, const void*
     }
     if (T == 0) return DORA_OK;
     DORA_HIP(launch_mag_scale(m, c, eff_eps(desc), p.g, nullptr, d_out, s));
+    // h = x A^T, written twice from the same accumulators: as it is (the saved tensor) and scaled by s,
+    // the low-rank operand of the K-concatenated product  [s h | x] [B | W]^T = s h B^T + x W^T
     void* h = saved_h ? saved_h : p.h;
     Seg s1{x, d_in, A, d_in, d_in};
-    DORA_HIP(contract(DORA_BF16, true, true, T, r, &s1, 1, 1.f, h, r, false, DORA_K_GEMM_H, s));
-    Seg segs[2] = {{h, r, B, r, r}, {x, d_in, W, d_in, d_in}};
+    GemmArgs gh = bf16_args(true, true, T, r, &s1, 1, 1.f, h, r, false, 0);
+    gh.c2 = p.hs;
+    gh.alpha2 = desc->s;
+    DORA_HIP(launch_gemm_bf16(gh, DORA_K_GEMM_H, s));
+    Seg segs[2] = {{p.hs, r, B, r, r}, {x, d_in, W, d_in, d_in}};
     GemmArgs g = bf16_args(true, true, T, d_out, segs, 2, 1.f, y, d_out, false, 0);
     g.epilogue = EPI_COMPOSE;
-    g.seg0_scale = desc->s;
     g.colscale = p.g;
     g.c2 = saved_inner;
     DORA_HIP(launch_gemm_bf16(g, DORA_K_GEMM_FUSED_FWD, s));

@@ -7,18 +7,20 @@
 // (both K-strided), and the factored-norm products of Sec. 2: U = W A^T with the row-dot epilogue
 // of Eq. 3 (U never leaves registers), G = A A^T (Eq. 4, split-K partials), and rowdot(B, B G).
 //
-// Structure (per workgroup): a BM x BN tile of C; K is walked in steps of BK through a ring of LDS
+// Structure (per workgroup): a BM x BN tile of C; K is walked in steps of 64 through rings of LDS
 // buffers that the global loads fill directly (buffer_load ... lds, 16 bytes per lane, no register
-// staging).  v_mfma_f32_32x32x16_bf16 on 64-wide wavefronts, each wave owning a (BM/WGM) x (BN/WGN)
-// sub-tile.  The N-side fragment is fed as the MFMA's first operand so that every lane ends up
+// staging).  A K step of 64 makes every row segment a load instruction fetches a full 128-byte line;
+// 64-byte segments stream at about two thirds of that rate.  v_mfma_f32_32x32x16_bf16 on 64-wide
+// wavefronts, four waves per workgroup, each owning a (BM/2) x (BN/2) sub-tile.  The N-side fragment is fed as the MFMA's first operand so that every lane ends up
 // holding four consecutive n for one m, which makes the epilogue's stores and row-dots
 // vector-friendly.  Workgroup ids are remapped so that each of the 8 XCDs (own L2 each) works on a
 // compact block of tiles, walked in groups of 8 tile-rows.
 //
-// Two tile shapes.  The 128 x 128 tile (4 waves, two workgroups per CU) steps K by 64, so that every
-// row segment a load instruction fetches is a full 128-byte line (64-byte segments stream at about
-// two thirds of that rate).  The 256 x 256 tile (8 waves) is bounded by LDS capacity instead: a ring
-// deep enough to cover the latency of loads that miss the L2 only fits with K steps of 32.
+// Two tile shapes.  128 x 128 (64 x 64 per wave, two workgroups per CU, which hide each other's
+// stalls) for the skinny products.  256 x 256 (128 x 128 per wave, accumulators in AGPRs, one wave
+// per SIMD, all 160 KB of LDS) for the large ones: the LDS path of a SIMD moves one 16-byte-per-lane
+// fragment read in about the time of one MFMA, and this is the shape with the fewest fragment reads
+// per MFMA; its memory instructions are interleaved with the MFMAs by hand.
 #include "common.hpp"
 
 #include <type_traits>
@@ -53,14 +55,13 @@ struct Tile {
     static_assert(LDS_BYTES <= 160 * 1024, "LDS of a gfx950 CU");
     static constexpr int a_slot_off(int s) { return SPLIT_RING ? s * A_BYTES : s * STAGE_BYTES; }
     static constexpr int b_slot_off(int s) { return SPLIT_RING ? A_STAGES * A_BYTES + s * B_BYTES : s * STAGE_BYTES + A_BYTES; }
-    static_assert(BK == 32 || BK == 64, "LDS layouts exist for K steps of 32 and 64");
+    static_assert(BK == 64, "the LDS layouts are written for K steps of 64");
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
-    static_assert(WAVES == 4 || WAVES == 8, "schedules exist for 4 and 8 waves");
+    static_assert(WAVES == 4, "the schedules are written for four waves");
     static_assert((BM * CPR) % THREADS == 0 && (BN * CPR) % THREADS == 0, "load plan must divide evenly");
 };
 
-typedef Tile<256, 256, 2, 4, 32, 4> TileBig;      // 512 threads, 4 x 32 KB of LDS, 128 accumulator registers per lane
-typedef Tile<256, 256, 2, 2, 64, 2> TileBig4;     // 256 threads, (3 + 2) x 32 KB of LDS, 256 accumulator registers (AGPRs) per lane
+typedef Tile<256, 256, 2, 2, 64, 2> TileBig;      // 256 threads, (3 + 2) x 32 KB of LDS, 256 accumulator registers (AGPRs) per lane
 typedef Tile<128, 128, 2, 2, 64, 2> TileMed;      // 256 threads, 2 x 32 KB of LDS, two workgroups fit a CU
 typedef Tile<128, 128, 2, 2, 64, 4> TileMedDeep;  // the same with a ring of four, for launches of at most one workgroup per CU
 
@@ -73,21 +74,21 @@ typedef __attribute__((address_space(3))) void* lds_void_ptr_t;
 // The LDS serves a 16-byte-per-lane access 16 lanes at a time, and those 16 lanes must touch 16
 // different 16-byte slots modulo 256 bytes.
 //
-// K-contiguous operand: [rows][BK] bf16.  With 128-byte rows (BK = 64) the chunk index is XORed with
-// row/2, with 64-byte rows (BK = 32) with row/4: the 16 rows one group of lanes reads (same logical
-// chunk) then cover all 16 slots.
+// K-contiguous operand: [rows][64] bf16, 128 bytes per row, the chunk index XORed with row/2: the 16
+// rows one group of lanes reads (same logical chunk) then cover all 16 slots.
 template <int BK>
 __device__ __forceinline__ int kc_swizzle(int row)
 {
-    return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3);
+    static_assert(BK == 64, "swizzle of 128-byte rows");
+    return (row >> 1) & 7;
 }
 template <int BK>
 __device__ __forceinline__ int lds_off(int row, int k)
 {
     return row * (BK * 2) + ((((k >> 3) ^ kc_swizzle<BK>(row)) & (BK / 8 - 1)) << 4) + ((k & 7) << 1);
 }
-// K-strided operand: kept as loaded, [BK][ROWS] bf16 (the layout does not depend on BK); chunks of 8 rows XORed with 4*(k mod 4) so the
-// four k-rows one transposing read touches fall into different slots.
+// K-strided operand: kept as loaded, [BK][ROWS] bf16; chunks of 8 rows XORed with 4*(k mod 4) so the four
+// k-rows one transposing read touches fall into different slots.
 template <int ROWS>
 __device__ __forceinline__ int lds_off_ks(int row, int k)
 {
@@ -331,21 +332,6 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
 #pragma unroll
     for (int i = 0; i < MT; ++i) bsq[i] = 0.f;
     const bool want_bsq = (EPI == EPI_ROWDOT) && (p.base_sq_partial != nullptr) && (tc.tn == 0);
-    // K steps of segment 0 inside this workgroup's range; when they are done the accumulators may be
-    // rescaled once (used to apply s to the low-rank segment of the K-concatenated forward)
-    const int seg0_steps = (t_end < kt0_total ? t_end : kt0_total) - t_begin;
-    // only the compose epilogue (K-concatenated forward) uses the rescale; elsewhere the code is compiled out
-    const bool rescale = (EPI == EPI_COMPOSE) && (p.seg0_scale != 0.f) && (p.nseg > 1);
-    auto rescale_acc = [&]() {
-        const float f = p.seg0_scale;
-#pragma unroll
-        for (int i = 0; i < MT; ++i)
-#pragma unroll
-            for (int j = 0; j < NT; ++j)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) acc[i][j][e] *= f;
-    };
-
     typedef OperandLoader<BM, BK, T::NLA, T::WAVES, A_KC> LA;
     typedef OperandLoader<BN, BK, T::NLB, T::WAVES, B_KC> LB;
     // One cursor per operand; each moves to the next segment (or to "exhausted") on its own.
@@ -442,62 +428,7 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
     };
 
     bf16x8_t a0[MT], b0[NT], a1[MT], b1[NT];
-    if constexpr (T::WAVES == 8) {
-        // Ping-pong (two waves per SIMD).  The waves form two groups of four, one wave of each group
-        // on every SIMD.  Time is cut into phases separated by workgroup barriers; in each phase one
-        // group runs the 16 MFMAs of a K step (of 32) from registers while the other reads the
-        // fragments of its next step from LDS and issues its share of the global loads, then the roles
-        // swap:
-        //     phase 2u   : group 0 multiplies step u   | group 1 fetches step u
-        //     phase 2u+1 : group 0 fetches step u+1    | group 1 multiplies step u
-        // so the matrix pipe of every SIMD always has one wave feeding it and the memory instructions
-        // of the other wave issue in its shadow.  Barriers are bare s_barriers with explicit counter
-        // waits (a fencing barrier would wait for every load in flight).
-        static_assert(KSTEPS == 2, "a ping-pong phase covers a K step of two MFMA k-steps");
-        if (nsteps > 0) {
-#pragma unroll
-            for (int u = 0; u < STAGES - 1; ++u) issue(u);
-        }
-        const int grp_id = wave >> 2;
-        auto fetch = [&](int u) {   // fragments of step u -> registers; refill the slot step u-1 used
-            frags(K0{}, a0, b0, u % STAGES);
-            frags(K1{}, a1, b1, u % STAGES);
-            issue((u + STAGES - 1) % STAGES);
-        };
-        auto compute = [&](int u) {
-            wait_lgkmcnt<0>();
-            __builtin_amdgcn_sched_barrier(0);
-            __builtin_amdgcn_s_setprio(1);
-            mma(a0, b0, 2 * u);
-            mma(a1, b1, 2 * u + 1);
-            __builtin_amdgcn_s_setprio(0);
-            __builtin_amdgcn_sched_barrier(0);
-            if (rescale && u == seg0_steps - 1) rescale_acc();
-        };
-        // every wave: its share of step 0 has landed; barrier: all of step 0 has landed
-        wait_vmcnt<(STAGES - 2) * LPT>();
-        __builtin_amdgcn_s_barrier();
-        if (grp_id == 0) {
-            if (nsteps > 0) fetch(0);
-            for (int u = 0; u < nsteps; ++u) {
-                __builtin_amdgcn_s_barrier();          // starts phase 2u
-                compute(u);
-                wait_vmcnt<(STAGES - 2) * LPT>();      // own share of step u+1 landed
-                __builtin_amdgcn_s_barrier();          // starts phase 2u+1: step u+1 complete, slot u free
-                if (u + 1 < nsteps) fetch(u + 1);
-            }
-        } else {
-            for (int u = 0; u < nsteps; ++u) {
-                __builtin_amdgcn_s_barrier();          // starts phase 2u
-                fetch(u);
-                wait_vmcnt<(STAGES - 2) * LPT>();
-                wait_lgkmcnt<0>();                     // own reads of slot u done before group 0 may refill it
-                __builtin_amdgcn_s_barrier();          // starts phase 2u+1
-                compute(u);
-            }
-        }
-        wait_vmcnt<0>();
-    } else if constexpr (T::SPLIT_RING) {
+    if constexpr (T::SPLIT_RING) {
         // Four waves, one per SIMD, each owning 128 x 128 of the tile (accumulators in the AGPR half of
         // the register file).  This shape needs the fewest LDS bytes per MFMA (eight fragment reads feed
         // sixteen MFMAs), which matters because the LDS path of a SIMD moves a 16-byte-per-lane read in
@@ -592,7 +523,6 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
             __builtin_amdgcn_sched_barrier(0);          // no MFMA may move above the waits
             // k-step 3 and the first fragments of step u+1; N side of step u+2, first half
             burst(K0{}, SideB{}, I0{}, IHB{}, a1, b1, a0, b0, sa1, sb1, smem + T::b_slot_off(u & 1));
-            if (rescale && u == seg0_steps - 1) rescale_acc();
             const int t = sa_cur;
             sa_cur = sa_nxt; sa_nxt = sa_fill; sa_fill = t;
         }
@@ -619,7 +549,6 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
             __builtin_amdgcn_sched_barrier(0);
             issue((u + STAGES - 1) % STAGES);
             if (u > 0) mma(a1, b1, KSTEPS * u - 1);      // its fragments were complete before the barrier
-            if (rescale && u == seg0_steps) rescale_acc();   // step u-1 was the last of segment 0
             __builtin_amdgcn_sched_barrier(0);
             static_for<KSTEPS / 2>([&](auto qt) {
                 constexpr int q = decltype(qt)::value;
@@ -643,7 +572,6 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
         wait_lgkmcnt<0>();
         __builtin_amdgcn_sched_barrier(0);
         if (nsteps > 0) mma(a1, b1, KSTEPS * nsteps - 1);
-        if (rescale && nsteps == seg0_steps && nsteps > 0) rescale_acc();
     }
     __syncthreads();
 
@@ -706,7 +634,8 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
                 cs[j][b] = (ng < p.N) ? *reinterpret_cast<const float4*>(p.colscale + ng) : make_float4(0.f, 0.f, 0.f, 0.f);
             }
     }
-    const int npass = (EPI == EPI_COMPOSE && p.c2 != nullptr) ? 2 : 1;
+    // EPI_STORE_BF16 with a second output: pass 1 writes alpha2 * acc to C2
+    const int npass = ((EPI == EPI_COMPOSE || EPI == EPI_STORE_BF16) && p.c2 != nullptr) ? 2 : 1;
     for (int pass = 0; pass < npass; ++pass) {
     char* cbase = reinterpret_cast<char*>(pass == 0 ? p.c : p.c2) +
                   (p.ksplit > 1 ? (int64_t)tc.z * p.M * p.ldc * ESZ : 0);
@@ -724,8 +653,9 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
                     v0 = g4.x * acc[i][j][b * 4 + 0]; v1 = g4.y * acc[i][j][b * 4 + 1];
                     v2 = g4.z * acc[i][j][b * 4 + 2]; v3 = g4.w * acc[i][j][b * 4 + 3];
                 } else {
-                    v0 = p.alpha * acc[i][j][b * 4 + 0]; v1 = p.alpha * acc[i][j][b * 4 + 1];
-                    v2 = p.alpha * acc[i][j][b * 4 + 2]; v3 = p.alpha * acc[i][j][b * 4 + 3];
+                    const float al = (pass == 0) ? p.alpha : p.alpha2;
+                    v0 = al * acc[i][j][b * 4 + 0]; v1 = al * acc[i][j][b * 4 + 1];
+                    v2 = al * acc[i][j][b * 4 + 2]; v3 = al * acc[i][j][b * 4 + 3];
                 }
                 if (OUT_BF16) {
                     uint2 o;
@@ -774,11 +704,6 @@ hipError_t launch_one(const GemmArgs& a, const GemmArgs* b, hipStream_t stream)
     return hipGetLastError();
 }
 
-// 256 x 256 tile per epilogue: the compose epilogue rescales the accumulators between its two K
-// segments, which does not fit beside 256 accumulator registers per lane, so it keeps the 8-wave tile.
-template <int EPI> struct BigTileFor { typedef TileBig4 type; };
-template <> struct BigTileFor<EPI_COMPOSE> { typedef TileBig type; };
-
 bool use_big(const GemmArgs& a)
 {
     // the large tile pays off once it still yields a few tiles per CU
@@ -795,7 +720,7 @@ hipError_t dispatch(const GemmArgs& a, const GemmArgs* b, hipStream_t stream)
     (deep ? launch_one<TileMedDeep, AKC, BKC, E>(a, b, stream) : launch_one<TileMed, AKC, BKC, E>(a, b, stream))
 #define DORA_GEMM_CASE(AKC, BKC, E)                                                     \
     if (a.a_kcontig == (AKC) && a.b_kcontig == (BKC) && a.epilogue == (E))              \
-        return big ? launch_one<typename BigTileFor<E>::type, AKC, BKC, E>(a, b, stream) : DORA_GEMM_MED(AKC, BKC, E);
+        return big ? launch_one<TileBig, AKC, BKC, E>(a, b, stream) : DORA_GEMM_MED(AKC, BKC, E);
     DORA_GEMM_CASE(true, true, EPI_STORE_BF16)
     DORA_GEMM_CASE(true, false, EPI_STORE_BF16)
     DORA_GEMM_CASE(true, true, EPI_COMPOSE)
