@@ -89,6 +89,68 @@ def cpu_baseline(cfg, inp, sample_tokens):
                       f"{cfg.tokens} tokens, {dt:.1f} s"}
 
 
+NORM_SWEEP_SHAPES = ((4096, 4096), (8192, 8192), (4096, 11008), (8192, 28672))   # shapes of Table 5
+NORM_SWEEP_RANKS = (16, 64, 128, 256, 384, 512, 768)
+
+
+def norm_sweep(reps: int):
+    """Rank sweep of the factored norm in isolation (the experiment of Sec. 5.6 / Table 5 on this machine).
+
+    For every shape and rank: dora_norm, dora_norm_cached (base term read from a [d_out] cache), the library's
+    scratch against one dense [d_out, d_in] temporary, and, for context only, the dense route in plain PyTorch
+    ops on the same GPU (W + s * (B @ A), then a row norm: the computation the factored form replaces).
+    Weights are seeded synthetic bf16 with the stated distributions.  Prints one JSON line.
+    """
+    import torch
+    from paper_2603_22276_amd import binding as D
+    dev = "cuda:0"
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(260322276)
+    bf = torch.bfloat16
+
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps   # microseconds per call
+
+    rows = []
+    for d_out, d_in in NORM_SWEEP_SHAPES:
+        W = (torch.randn(d_out, d_in, device=dev, generator=gen) * d_in ** -0.5).to(bf)
+        base_sq = torch.empty(d_out, dtype=torch.float32, device=dev)
+        c = torch.empty(d_out, dtype=torch.float32, device=dev)
+        for r in NORM_SWEEP_RANKS:
+            s = 32.0 / r ** 0.5
+            A = (torch.randn(r, d_in, device=dev, generator=gen) * d_in ** -0.5).to(bf)
+            B = (torch.randn(d_out, r, device=dev, generator=gen) * 1e-3).to(bf)
+            desc = D.make_desc(d_out, d_in, r, 0, D.DORA_BF16, s)
+            ws_bytes = D.dora_workspace_bytes(desc, D.PHASE_NORM)
+            ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+            D.dora_base_sq(desc, W, base_sq)
+            t_norm = timed(lambda: D.dora_norm(desc, W, A, B, c, ws))
+            t_cached = timed(lambda: D.dora_norm_cached(desc, base_sq, W, A, B, c, ws))
+            t_dense = timed(lambda: torch.linalg.vector_norm((W + s * (B @ A)).float(), dim=1))
+            flops = 2.0 * d_out * d_in * (r + 1) + 2.0 * r * r * d_in + 2.0 * d_out * r * r
+            nbytes = 2.0 * (d_out * d_in + r * d_in + d_out * r) + 4.0 * d_out
+            rows.append({
+                "d_out": d_out, "d_in": d_in, "r": r,
+                "norm_us": round(t_norm, 1), "norm_cached_us": round(t_cached, 1), "dense_pytorch_us": round(t_dense, 1),
+                "tflops": round(flops / t_norm / 1e6, 1), "gbs": round(nbytes / t_norm / 1e3, 1),
+                "frac_mfma": round(flops / t_norm / 1e6 / PEAK_BF16_TFLOPS, 3), "frac_hbm": round(nbytes / t_norm / 1e3 / PEAK_HBM_GBS, 3),
+                "scratch_bytes": int(ws_bytes), "dense_temp_bytes": 2 * d_out * d_in,
+            })
+            del A, B, ws
+        del W
+    print(json.dumps({"metric": "dora_norm latency over rank, in isolation", "unit": "us", "dtype": "bf16",
+                      "data": "synthetic", "reps": reps, "rows": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -100,11 +162,16 @@ def main():
                     help="forward through dora_forward_fused (compose folded into the GEMM epilogue) instead of the\n"
                          "base / lora / compose sequence")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
+    ap.add_argument("--norm-sweep", action="store_true",
+                    help="instead of the step benchmark: time dora_norm alone over ranks and the weight shapes of Table 5")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs the DoRA module on ONE GPU; --gpus N with N > 1 is not supported "
               "(no collectives are part of the path).", file=sys.stderr)
         sys.exit(2)
+    if args.norm_sweep:
+        norm_sweep(max(args.steps, 1))
+        return
 
     import torch
     from paper_2603_22276_amd import binding as D

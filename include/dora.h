@@ -74,6 +74,20 @@ dora_status dora_norm(const dora_desc* desc, const void* W, const void* A, const
                       float* w_norm, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Cached base term (Sec. 2.3: W is frozen, so the rank-independent term of Eq. 2 can be
+ * computed once and kept in a [d_out] buffer).
+ *   dora_base_sq     : base_sq[j] = sum_k W[j,k]^2, fp32 accumulation of the exact products.
+ *                      W : device, const, `dtype` [d_out, d_in].  base_sq : device, out, fp32 [d_out].
+ *                      Needs no workspace; desc->r and desc->tokens are not read.
+ *   dora_norm_cached : dora_norm with that buffer as the base term: W is read once (for the cross
+ *                      term) and never squared.  Same workspace, outputs and error behaviour as
+ *                      dora_norm; the caller owns base_sq and must recompute it if W changes.
+ */
+dora_status dora_base_sq(const dora_desc* desc, const void* W, float* base_sq, void* stream);
+dora_status dora_norm_cached(const dora_desc* desc, const float* base_sq, const void* W, const void* A,
+                             const void* B, float* w_norm, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Magnitude scale of Eq. 6: g = m / max(w_norm, eps), and the explicit small
  * correction gm1 = g - 1 of Sec. 3.1, formed as (m - cc)/cc with cc = max(w_norm, eps)
  * so that it does not suffer the rounding of g.  g or gm1 may be NULL (not both).

@@ -196,13 +196,15 @@ hipError_t contract(int dtype, bool a_kc, bool b_kc, int M, int N, const Seg* se
 
 // ------------------------------------------------------------------------------------------------
 // factored norm (Sec. 2, Algorithm 1)
+// base_sq != nullptr: the base term of Eq. 2 comes from the caller's cache and W is not squared again
 dora_status norm_impl(const dora_desc* d, const void* W, const void* A, const void* B, float* c, const NormPlan& n,
-                      hipStream_t st)
+                      hipStream_t st, const float* base_sq = nullptr)
 {
     const int d_out = (int)d->d_out, d_in = (int)d->d_in, r = (int)d->r;
     if (d->s == 0.f) {  // scale-is-zero fast path: no U, no G
-        if (d->dtype == DORA_BF16) DORA_HIP(launch_rownorm_s0_bf16((const bf16_t*)W, c, d_out, d_in, st));
-        else DORA_HIP(launch_rownorm_f32((const float*)W, nullptr, nullptr, nullptr, 0.0, c, d_out, d_in, r, st));
+        if (base_sq) DORA_HIP(launch_norm_final(base_sq, 1, nullptr, 0, nullptr, 0, 0.0, c, d_out, st));
+        else if (d->dtype == DORA_BF16) DORA_HIP(launch_rownorm_s0_bf16((const bf16_t*)W, c, d_out, d_in, false, st));
+        else DORA_HIP(launch_rownorm_f32((const float*)W, nullptr, nullptr, nullptr, nullptr, 0.0, c, d_out, d_in, r, false, st));
         return DORA_OK;
     }
     if (d->dtype == DORA_BF16) {
@@ -212,7 +214,7 @@ dora_status norm_impl(const dora_desc* d, const void* W, const void* A, const vo
         g.seg[0] = GemmSeg{(const bf16_t*)W, (const bf16_t*)A, d_in, d_in, d_in};
         g.nseg = 1; g.M = d_out; g.N = r; g.a_kcontig = 1; g.b_kcontig = 1; g.epilogue = EPI_ROWDOT; g.alpha = 1.f;
         g.ksplit = n.ks_u; g.rowdot = (const bf16_t*)B; g.ld_rowdot = r; g.rowdot_partial = n.cross_p;
-        g.base_sq_partial = n.base_p;
+        g.base_sq_partial = base_sq ? nullptr : n.base_p;
         DORA_HIP(launch_gemm_bf16(g, DORA_K_NORM_CROSS, st));
         // Gram matrix (Eq. 4): split-K partials, then a fixed-order sum and the hi/lo bf16 expansion
         memset(&g, 0, sizeof(g));
@@ -229,8 +231,8 @@ dora_status norm_impl(const dora_desc* d, const void* W, const void* A, const vo
         g.nseg = 2; g.M = d_out; g.N = r; g.a_kcontig = 1; g.b_kcontig = 1; g.epilogue = EPI_ROWDOT; g.alpha = 1.f;
         g.ksplit = 1; g.rowdot = (const bf16_t*)B; g.ld_rowdot = r; g.rowdot_partial = n.ba_p; g.tag = 1;
         DORA_HIP(launch_gemm_bf16(g, DORA_K_BA_SQ, st));
-        DORA_HIP(launch_norm_final(n.base_p, n.ks_u, n.cross_p, n.ks_u * n.tiles_n, n.ba_p, n.tiles_n, (double)d->s, c,
-                                   d_out, st));
+        DORA_HIP(launch_norm_final(base_sq ? base_sq : n.base_p, base_sq ? 1 : n.ks_u, n.cross_p, n.ks_u * n.tiles_n,
+                                   n.ba_p, n.tiles_n, (double)d->s, c, d_out, st));
         return DORA_OK;
     }
     // fp32: Algorithm 1 with one chunk spanning d_in; U [d_out, r], G [r, r], BG [d_out, r] in scratch
@@ -240,7 +242,8 @@ dora_status norm_impl(const dora_desc* d, const void* W, const void* A, const vo
     DORA_HIP(contract(DORA_F32, true, true, r, r, &sg, 1, 1.f, n.G, r, true, DORA_K_GRAM, st));
     Seg sb{B, r, n.G, r, r};  // (B G)[j,l] = sum_k B[j,k] G[k,l]: N-side operand K-strided
     DORA_HIP(contract(DORA_F32, true, false, d_out, r, &sb, 1, 1.f, n.BG, r, true, DORA_K_BA_SQ, st));
-    DORA_HIP(launch_rownorm_f32((const float*)W, (const float*)B, n.U, n.BG, (double)d->s, c, d_out, d_in, r, st));
+    DORA_HIP(launch_rownorm_f32((const float*)W, base_sq, (const float*)B, n.U, n.BG, (double)d->s, c, d_out, d_in, r,
+                                false, st));
     return DORA_OK;
 }
 
@@ -361,6 +364,35 @@ dora_status dora_norm(const dora_desc* desc, const void* W, const void* A, const
     Bump b(ws);
     plan_norm(desc, b, n);
     return norm_impl(desc, W, A, B, w_norm, n, (hipStream_t)stream);
+}
+
+dora_status dora_base_sq(const dora_desc* desc, const void* W, float* base_sq, void* stream)
+{
+    dora_status st = check_desc(desc, false);
+    if (st != DORA_OK) return st;
+    const int64_t mult = desc->dtype == DORA_BF16 ? 8 : 4;
+    if (desc->d_in < mult || desc->d_in % mult || desc->d_out * desc->d_in >= MAX_ELEMS) return DORA_ERR_SHAPE;
+    DORA_REQ_PTR(W); DORA_REQ_PTR(base_sq);
+    const int d_out = (int)desc->d_out, d_in = (int)desc->d_in;
+    hipStream_t s = (hipStream_t)stream;
+    if (desc->dtype == DORA_BF16) DORA_HIP(launch_rownorm_s0_bf16((const bf16_t*)W, base_sq, d_out, d_in, true, s));
+    else DORA_HIP(launch_rownorm_f32((const float*)W, nullptr, nullptr, nullptr, nullptr, 0.0, base_sq, d_out, d_in, 0, true, s));
+    return DORA_OK;
+}
+
+dora_status dora_norm_cached(const dora_desc* desc, const float* base_sq, const void* W, const void* A, const void* B,
+                             float* w_norm, void* ws, size_t ws_bytes, void* stream)
+{
+    dora_status st = check_desc(desc, true);
+    if (st != DORA_OK) return st;
+    DORA_REQ_PTR(base_sq); DORA_REQ_PTR(W); DORA_REQ_PTR(A); DORA_REQ_PTR(B); DORA_REQ_PTR(w_norm);
+    Bump sizing(nullptr);
+    NormPlan n;
+    plan_norm(desc, sizing, n);
+    if ((st = check_ws(ws, ws_bytes, sizing.off)) != DORA_OK) return st;
+    Bump b(ws);
+    plan_norm(desc, b, n);
+    return norm_impl(desc, W, A, B, w_norm, n, (hipStream_t)stream, base_sq);
 }
 
 dora_status dora_mag_scale(const dora_desc* desc, const float* m, const float* w_norm, float* g, float* gm1,

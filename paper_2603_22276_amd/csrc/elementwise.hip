@@ -93,16 +93,20 @@ __global__ void gram_reduce_kernel(const float* __restrict__ p, int ksplit, int 
 }
 
 // fp32 configuration: the three terms of Eq. 2 for one row per wavefront, from U = W A^T and BG = B G.
-__global__ void rownorm_f32_kernel(const float* __restrict__ W, const float* __restrict__ B, const float* __restrict__ U,
+// base_in != nullptr: the base term is read from it instead of being summed from W (Sec. 2.3: W is frozen, so
+// its squared row norms can be computed once).  squared: write the radicand itself, not its root.
+__global__ void rownorm_f32_kernel(const float* __restrict__ W, const float* __restrict__ base_in,
+                                   const float* __restrict__ B, const float* __restrict__ U,
                                    const float* __restrict__ BG, float two_s, float s2, float* __restrict__ c,
-                                   int d_out, int d_in, int r)
+                                   int d_out, int d_in, int r, bool squared)
 {
     int lane = threadIdx.x & 63;
     int row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (row >= d_out) return;
     float base_sq = 0.f, cross = 0.f, ba = 0.f;
     const float* w = W + (int64_t)row * d_in;
-    for (int k = lane; k < d_in; k += 64) { float v = w[k]; base_sq = fmaf(v, v, base_sq); }
+    if (!base_in)
+        for (int k = lane; k < d_in; k += 64) { float v = w[k]; base_sq = fmaf(v, v, base_sq); }
     if (U) {
         const float* b = B + (int64_t)row * r;
         const float* u = U + (int64_t)row * r;
@@ -115,14 +119,16 @@ __global__ void rownorm_f32_kernel(const float* __restrict__ W, const float* __r
         ba += __shfl_xor(ba, o);
     }
     if (lane == 0) {
+        if (base_in) base_sq = base_in[row];
         float rad = base_sq + two_s * cross + s2 * ba;
         rad = (rad < 0.f) ? 0.f : rad;
-        c[row] = __fsqrt_rn(rad);
+        c[row] = squared ? rad : __fsqrt_rn(rad);
     }
 }
 
 // s == 0 (Algorithm 1, notes): the norm is the row norm of W alone.  One wavefront per row, bf16 storage.
-__global__ void rownorm_s0_bf16_kernel(const bf16_t* __restrict__ W, float* __restrict__ c, int d_out, int d_in)
+__global__ void rownorm_s0_bf16_kernel(const bf16_t* __restrict__ W, float* __restrict__ c, int d_out, int d_in,
+                                       bool squared)
 {
     int lane = threadIdx.x & 63;
     int row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
@@ -137,7 +143,7 @@ __global__ void rownorm_s0_bf16_kernel(const bf16_t* __restrict__ W, float* __re
         for (int i = 0; i < 8; ++i) acc = fmaf(f[i], f[i], acc);
     }
     for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
-    if (lane == 0) c[row] = __fsqrt_rn(acc);
+    if (lane == 0) c[row] = squared ? acc : __fsqrt_rn(acc);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -330,21 +336,21 @@ hipError_t launch_gram_reduce(const float* partials, int ksplit, int r, float* G
     return hipGetLastError();
 }
 
-hipError_t launch_rownorm_s0_bf16(const bf16_t* W, float* c, int d_out, int d_in, hipStream_t st)
+hipError_t launch_rownorm_s0_bf16(const bf16_t* W, float* c, int d_out, int d_in, bool squared, hipStream_t st)
 {
     if (d_out == 0) return hipSuccess;
     TraceScope ts(DORA_K_NORM_FINAL, st);
-    rownorm_s0_bf16_kernel<<<dim3((d_out + 3) / 4), dim3(256), 0, st>>>(W, c, d_out, d_in);
+    rownorm_s0_bf16_kernel<<<dim3((d_out + 3) / 4), dim3(256), 0, st>>>(W, c, d_out, d_in, squared);
     return hipGetLastError();
 }
 
-hipError_t launch_rownorm_f32(const float* W, const float* B, const float* U, const float* BG, double s, float* c,
-                              int d_out, int d_in, int r, hipStream_t st)
+hipError_t launch_rownorm_f32(const float* W, const float* base_in, const float* B, const float* U, const float* BG,
+                              double s, float* c, int d_out, int d_in, int r, bool squared, hipStream_t st)
 {
     if (d_out == 0) return hipSuccess;
     TraceScope ts(DORA_K_NORM_FINAL, st);
-    rownorm_f32_kernel<<<dim3((d_out + 3) / 4), dim3(256), 0, st>>>(W, B, U, BG, (float)(2.0 * s), (float)(s * s), c,
-                                                                    d_out, d_in, r);
+    rownorm_f32_kernel<<<dim3((d_out + 3) / 4), dim3(256), 0, st>>>(W, base_in, B, U, BG, (float)(2.0 * s),
+                                                                    (float)(s * s), c, d_out, d_in, r, squared);
     return hipGetLastError();
 }
 

@@ -91,6 +91,12 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.dora_compose_backward(ctypes.byref(d), FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, big, None) == 1
     assert L.dora_mag_scale(ctypes.byref(d), FAKE, FAKE, None, None, None) == 1
     assert L.dora_project(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, None) == 1
+    # cached base term
+    assert L.dora_base_sq(ctypes.byref(d), None, FAKE, None) == 1
+    assert L.dora_base_sq(ctypes.byref(d), FAKE, FAKE + 2, None) == 3
+    assert L.dora_base_sq(ctypes.byref(desc(d_in=100)), FAKE, FAKE, None) == 2
+    assert L.dora_norm_cached(ctypes.byref(d), None, FAKE, FAKE, FAKE, FAKE, FAKE, big, None) == 1
+    assert L.dora_norm_cached(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, ws_n - 1, None) == 5
 
 
 def test_binding_refuses_host_tensors():

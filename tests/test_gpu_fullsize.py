@@ -105,3 +105,25 @@ def test_c4_mlp_pair_recompute_sampled(cfg):
 def test_c5_decoder_modules_recompute_sampled(module_index, r):
     cfg = I.c5_module(module_index, r)
     check_module_sampled(cfg, recompute=True, n_tok=24, n_out=24)
+
+
+@pytest.mark.parametrize("d_out,d_in,r", [(8192, 28672, 384), (4096, 11008, 384), (8192, 8192, 768), (4096, 4096, 16)],
+                         ids=["moe_8192x28672_r384", "4096x11008_r384", "8192x8192_r768", "4096x4096_r16"])
+def test_norm_at_the_rank_sweep_shapes_sampled_rows(d_out, d_in, r):
+    # shapes of Table 5; rows of the norm are independent, so the dense definition is evaluated on sampled rows
+    for cfg in (I.DoraConfig("sweep", d_out, d_in, r, 8, "bf16", 32.0, 1e-3, seed_offset=9100 + r),
+                I.stress(I.DoraConfig("sweep_stress", d_out, d_in, r, 8, "bf16", 32.0, 1e-3, seed_offset=9200 + r))):
+        mod = G.Module(cfg)
+        rows = sample(d_out, 96, 3)
+        A = mod.f64("A")
+        Wr = I.to_f64(mod.inp["W"][rows])
+        Br = I.to_f64(mod.inp["B"][rows])
+        ref = O.dense_row_norm(Wr, A, Br, float(mod.inp["s"]))
+        G.assert_norm_close(pick(mod.norm(), rows), ref, G.TOL["bf16"]["norm"])
+        base_sq = G.empty_f32(d_out)
+        c = G.empty_f32(d_out)
+        from paper_2603_22276_amd import binding as D
+        D.dora_base_sq(mod.desc, mod.W, base_sq)
+        D.dora_norm_cached(mod.desc, base_sq, mod.W, mod.A, mod.B, c, G.workspace(mod.desc, D.PHASE_NORM))
+        G.assert_norm_close(pick(c, rows), ref, G.TOL["bf16"]["norm"])
+        del mod

@@ -49,6 +49,45 @@ def test_norm_matches_dense_oracle(cfg):
     G.assert_norm_close(c, ref, G.TOL[cfg.dtype]["norm"])
 
 
+@pytest.mark.parametrize("cfg", SMALL, ids=IDS)
+def test_cached_base_term_and_norm_from_it(cfg):
+    # Sec. 2.3: the base term is rank independent and W is frozen, so it may be computed once and reused.
+    # base_sq is a sum of exactly representable products in fp32: checked tightly against the fp64 sum;
+    # the norm assembled from the cached term is held to the same bar as dora_norm, against the dense definition.
+    mod = G.Module(cfg)
+    W = mod.f64("W")
+    base_sq = G.empty_f32(cfg.d_out)
+    D.dora_base_sq(mod.desc, mod.W, base_sq)
+    ref_sq = np.sum(W * W, axis=1)
+    got_sq = G.to_f64(base_sq)
+    assert np.all(np.isfinite(got_sq))
+    assert np.max(np.abs(got_sq - ref_sq) / ref_sq) <= 1e-5
+    c = G.empty_f32(cfg.d_out)
+    D.dora_norm_cached(mod.desc, base_sq, mod.W, mod.A, mod.B, c, G.workspace(mod.desc, D.PHASE_NORM))
+    ref = O.dense_row_norm(W, mod.f64("A"), mod.f64("B"), float(mod.inp["s"]))
+    G.assert_norm_close(G.to_f64(c), ref, G.TOL[cfg.dtype]["norm"])
+    # the cache is really what is used: a doubled base term must show up in the result
+    base_sq2 = base_sq * 4.0
+    D.dora_norm_cached(mod.desc, base_sq2, mod.W, mod.A, mod.B, c, G.workspace(mod.desc, D.PHASE_NORM))
+    terms = O.factored_norm_terms(W, mod.f64("A"), mod.f64("B"))
+    s = float(mod.inp["s"])
+    ref2 = np.sqrt(np.maximum(4.0 * terms["base_sq"] + 2.0 * s * terms["cross"] + s * s * terms["ba_sq"], 0.0))
+    G.assert_norm_close(G.to_f64(c), ref2, G.TOL[cfg.dtype]["norm"])
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_cached_norm_with_zero_scale(dtype):
+    mk = cfg_bf16 if dtype == "bf16" else cfg_f32
+    cfg = mk("s0", 264, 328, 24, 8, seed=21)
+    mod = G.Module(cfg)
+    desc = D.make_desc(cfg.d_out, cfg.d_in, cfg.r, cfg.tokens, G.dtype_code(dtype), 0.0, 0.0)
+    base_sq = G.empty_f32(cfg.d_out)
+    D.dora_base_sq(desc, mod.W, base_sq)
+    c = G.empty_f32(cfg.d_out)
+    D.dora_norm_cached(desc, base_sq, mod.W, mod.A, mod.B, c, G.workspace(desc, D.PHASE_NORM))
+    G.assert_norm_close(G.to_f64(c), np.linalg.norm(mod.f64("W"), axis=1), G.TOL[dtype]["norm"])
+
+
 def test_norm_low_rank_terms_matter_in_stress_variant():
     # guards the guard: in the stress variant dropping BA would be far outside tolerance
     cfg = I.stress(cfg_bf16("bf16_mid", 1024, 1536, 384, 640, seed=4))
