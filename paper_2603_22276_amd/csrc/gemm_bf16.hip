@@ -402,12 +402,7 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
     typedef std::integral_constant<int, 1> K1;
     typedef std::integral_constant<int, 2> K2;
     typedef std::integral_constant<int, 3> K3;
-    auto mma = [&](const bf16x8_t (&af)[MT], const bf16x8_t (&bfr)[NT], int kk) {
-#pragma unroll
-        for (int i = 0; i < MT; ++i)
-#pragma unroll
-            for (int j = 0; j < NT; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+    auto base_term = [&](const bf16x8_t (&af)[MT], int kk) {
         if (EPI == EPI_ROWDOT) {
             // base term of Eq. 2: sum of squares of the M-side rows, taken from the fragments
             // already in registers; the waves along N share the K steps between them
@@ -425,6 +420,14 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
                 }
             }
         }
+    };
+    auto mma = [&](const bf16x8_t (&af)[MT], const bf16x8_t (&bfr)[NT], int kk) {
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+        base_term(af, kk);
     };
 
     bf16x8_t a0[MT], b0[NT], a1[MT], b1[NT];
@@ -525,6 +528,76 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
             burst(K0{}, SideB{}, I0{}, IHB{}, a1, b1, a0, b0, sa1, sb1, smem + T::b_slot_off(u & 1));
             const int t = sa_cur;
             sa_cur = sa_nxt; sa_nxt = sa_fill; sa_fill = t;
+        }
+        wait_vmcnt<0>();
+        wait_lgkmcnt<0>();
+    } else if constexpr (STAGES >= 3) {
+        // 64 x 64 per wave, one workgroup per CU (launches of at most one workgroup per CU get this
+        // tile): with a single wave per SIMD and only four MFMAs per k-step, a fragment read issued one
+        // k-step ahead has not landed when its MFMAs are due.  Fragments are therefore read two k-steps
+        // ahead into four register sets (one per k-step of a K step), one fragment behind each MFMA,
+        // and the global loads of a K step follow the MFMAs of k-step 2.  The workgroup barrier sits in
+        // the middle of a K step: before k-step 2, whose MFMAs are interleaved with the first reads of
+        // the next K step.  By then every wave has consumed all fragments of the previous K step, so its
+        // buffer is refilled there.
+        constexpr int NM = MT * NT, NF = MT + NT;
+        static_assert(KSTEPS == 4 && NF <= NM && LPT % NM == 0, "deep-prefetch schedule assumptions");
+        bf16x8_t fa[4][MT], fb[4][NT];
+        // MFMAs of k-step KC (set KC); fragments of k-step KN (set KN) of ring slot `slot`; LOADS: the
+        // global loads of the cursor's K step into ring slot `fill`
+        auto burst = [&](auto kc_tag, auto kn_tag, auto loads_tag, int slot, int fill, int kk) {
+            constexpr int KC = decltype(kc_tag)::value, KN = decltype(kn_tag)::value;
+            constexpr bool LOADS = decltype(loads_tag)::value;
+            const uint32_t sa = smem_lds + T::a_slot_off(slot), sb = smem_lds + T::b_slot_off(slot);
+            static_for<NM>([&](auto nt) {
+                constexpr int n = decltype(nt)::value;
+                constexpr int i = n / NT, j = n % NT;
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[KC][j], fa[KC][i], acc[i][j], 0, 0, 0);
+                if constexpr (n < NF) read_frag(kn_tag, nt, fa[KN], fb[KN], sa, sb);
+                if constexpr (LOADS) {
+                    static_for<LPT / NM>([&](auto dt) {
+                        constexpr int t = n * (LPT / NM) + decltype(dt)::value;
+                        if constexpr (t < T::NLA) {
+                            ca.template issue_one<t>(smem + T::a_slot_off(fill), wave);
+                            if constexpr (t == T::NLA - 1) advance_a();
+                        } else {
+                            cb.template issue_one<t - T::NLA>(smem + T::b_slot_off(fill), wave);
+                            if constexpr (t == LPT - 1) advance_b();
+                        }
+                    });
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            base_term(fa[KC], kk);
+        };
+        typedef std::true_type Loads;
+        typedef std::false_type NoLoads;
+#pragma unroll
+        for (int u = 0; u < STAGES - 1; ++u) issue(u);
+        wait_vmcnt<(STAGES - 2) * LPT>();              // own share of step 0 landed
+        __builtin_amdgcn_s_barrier();
+        frags(K0{}, fa[0], fb[0], 0);
+        frags(K1{}, fa[1], fb[1], 0);
+        for (int u = 0; u < nsteps; ++u) {
+            const int slot = u % STAGES, next = (u + 1) % STAGES, fill = (u + STAGES - 1) % STAGES;
+            __builtin_amdgcn_sched_barrier(0);
+            wait_lgkmcnt<FRAG_OPS>();                  // set 0 landed; set 1 may still be in flight
+            __builtin_amdgcn_sched_barrier(0);
+            burst(K0{}, K2{}, NoLoads{}, slot, 0, 4 * u);
+            wait_lgkmcnt<FRAG_OPS>();
+            __builtin_amdgcn_sched_barrier(0);
+            burst(K1{}, K3{}, NoLoads{}, slot, 0, 4 * u + 1);
+            // own share of step u+1 landed (STAGES-3 later steps may be in flight); after the barrier it
+            // is visible to all, and the buffer of step u-1, whose last fragments every wave consumed
+            // before it got here, takes step u + STAGES - 1
+            wait_vmcnt<(STAGES - 3) * LPT>();
+            wait_lgkmcnt<FRAG_OPS>();                  // set 2 landed
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);          // no MFMA may move above the waits
+            burst(K2{}, K0{}, Loads{}, next, fill, 4 * u + 2);
+            wait_lgkmcnt<FRAG_OPS>();
+            __builtin_amdgcn_sched_barrier(0);
+            burst(K3{}, K1{}, NoLoads{}, next, 0, 4 * u + 3);
         }
         wait_vmcnt<0>();
         wait_lgkmcnt<0>();
