@@ -199,7 +199,7 @@ def main():
     fwd = D.dora_forward_fused if args.fused_forward else D.dora_forward
 
     def step():
-        fwd(desc, mod.x, mod.W, mod.A, mod.B, mod.m, None, y, h, inner, c, ws_f)
+        fwd(desc, mod.x, mod.W, mod.A, mod.B, mod.m, None, None, y, h, inner, c, ws_f)
         D.dora_backward(desc, mod.dy, mod.x, mod.W, mod.A, mod.B, mod.m, c, h, inner, dx, dA, dB, dm, ws_b)
 
     for _ in range(args.warmup):
@@ -254,7 +254,7 @@ def main():
     other_fwd = D.dora_forward if args.fused_forward else D.dora_forward_fused
 
     def other_step():
-        other_fwd(desc, mod.x, mod.W, mod.A, mod.B, mod.m, None, y, h, inner, c, ws_f)
+        other_fwd(desc, mod.x, mod.W, mod.A, mod.B, mod.m, None, None, y, h, inner, c, ws_f)
         D.dora_backward(desc, mod.dy, mod.x, mod.W, mod.A, mod.B, mod.m, c, h, inner, dx, dA, dB, dm, ws_b)
 
     for _ in range(2):

@@ -135,25 +135,28 @@ dora_status dora_project(const dora_desc* desc, const void* x, const void* W, co
  * base = x W^T, h = x A^T, lora = h B^T, compose;  y = base + delta = g (.) (base + s*lora).
  *   x [tokens, d_in], W, A, B : const `dtype`.   m : const fp32 [d_out].
  *   w_norm : const fp32 [d_out] or NULL (NULL: computed here into the workspace).
+ *   bias : const `dtype` [d_out] or NULL: bias of the frozen base layer.  It takes no part in the
+ *          compose (App. A item 2: subtracted before, re-added after), so it is added last:
+ *          y = base + delta + bias; inner and the backward are unaffected.
  *   y : out `dtype` [tokens, d_out].
  *   saved_h : out `dtype` [tokens, r] or NULL.   saved_inner : out `dtype` [tokens, d_out] or NULL.
  *   w_norm_out : out fp32 [d_out] or NULL (receives the norm used, for the backward call).
  */
 dora_status dora_forward(const dora_desc* desc, const void* x, const void* W, const void* A,
-                         const void* B, const float* m, const float* w_norm,
+                         const void* B, const float* m, const float* w_norm, const void* bias,
                          void* y, void* saved_h, void* saved_inner, float* w_norm_out,
                          void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Same result as dora_forward, computed without the base / lora round trip: one K-concatenated
- * contraction  inner = [s*h | x] [B | W]^T  (the low-rank segment first, its accumulators multiplied
- * by s, then the d_in segment on top) whose epilogue writes y = g (.) inner and, if asked, inner.
+ * contraction  inner = [s*h | x] [B | W]^T  (the h = x A^T product writes both h and s*h from its
+ * accumulators) whose epilogue writes y = g (.) inner (+ bias) and, if asked, inner.
  * The cancellation issue of Sec. 3.1 concerns the *delta* form only; g (.) inner taken from an fp32
  * accumulator has none.  DORA_BF16 descs only (DORA_ERR_DTYPE otherwise).  Arguments, workspace
  * (DORA_PHASE_FORWARD) and saved tensors exactly as for dora_forward.
  */
 dora_status dora_forward_fused(const dora_desc* desc, const void* x, const void* W, const void* A,
-                               const void* B, const float* m, const float* w_norm,
+                               const void* B, const float* m, const float* w_norm, const void* bias,
                                void* y, void* saved_h, void* saved_inner, float* w_norm_out,
                                void* ws, size_t ws_bytes, void* stream);
 

@@ -76,7 +76,8 @@ def adapted_weight(W, A, B, m, s, eps) -> np.ndarray:
 
 # --------------------------------------------------------------------------- forward
 
-def forward(x, W, A, B, m, s, eps, c: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
+def forward(x, W, A, B, m, s, eps, c: Optional[np.ndarray] = None,
+            bias: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
     """Whole forward of one module.
 
     base  = x W^T                  [T, d_out]
@@ -85,6 +86,10 @@ def forward(x, W, A, B, m, s, eps, c: Optional[np.ndarray] = None) -> Dict[str, 
     inner = s*lora + base          (the tensor Tier 1 saves for backward)
     delta = (g-1)*base + g*(s*lora)   (compose equation, App. A item 1)
     y     = base + delta           (what the caller of the module ends up with)
+
+    bias (App. A item 2): the frozen layer's bias is taken off its output before the
+    compose and put back afterwards, i.e. it is not scaled by g: y = base + delta + bias
+    with base the bias-free x W^T.
     """
     x, W, A, B, m = _f64(x), _f64(W), _f64(A), _f64(B), _f64(m)
     s = F64(s)
@@ -97,6 +102,8 @@ def forward(x, W, A, B, m, s, eps, c: Optional[np.ndarray] = None) -> Dict[str, 
     inner = s * lora + base
     delta = (g - 1.0)[None, :] * base + g[None, :] * (s * lora)
     y = base + delta
+    if bias is not None:
+        y = y + _f64(bias)[None, :]
     return {"c": c, "g": g, "base": base, "h": h, "lora": lora, "inner": inner, "delta": delta, "y": y}
 
 

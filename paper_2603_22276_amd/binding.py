@@ -60,7 +60,7 @@ def lib() -> ctypes.CDLL:
         L.dora_compose.argtypes = [dp, vp, vp, fp, fp, vp, ctypes.c_int, vp, vp]
         L.dora_compose_backward.argtypes = [dp, vp, vp, fp, fp, vp, fp, vp, sz, vp]
         L.dora_project.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp]
-        L.dora_forward.argtypes = [dp, vp, vp, vp, vp, fp, fp, vp, vp, vp, fp, vp, sz, vp]
+        L.dora_forward.argtypes = [dp, vp, vp, vp, vp, fp, fp, vp, vp, vp, vp, fp, vp, sz, vp]
         L.dora_forward_fused.argtypes = L.dora_forward.argtypes
         L.dora_backward.argtypes = [dp, vp, vp, vp, vp, vp, fp, fp, vp, vp, vp, fp, fp, fp, vp, sz, vp]
         L.dora_probe_copy.argtypes = [vp, vp, sz, vp]
@@ -160,13 +160,13 @@ def dora_project(desc, x, W, A, B, base, h, lora, stream=None) -> None:
                               _stream(stream)), "dora_project")
 
 
-def dora_forward(desc, x, W, A, B, m, w_norm, y, saved_h, saved_inner, w_norm_out, ws, stream=None) -> None:
-    _check(lib().dora_forward(ctypes.byref(desc), _p(x), _p(W), _p(A), _p(B), _p(m), _p(w_norm), _p(y), _p(saved_h),
+def dora_forward(desc, x, W, A, B, m, w_norm, bias, y, saved_h, saved_inner, w_norm_out, ws, stream=None) -> None:
+    _check(lib().dora_forward(ctypes.byref(desc), _p(x), _p(W), _p(A), _p(B), _p(m), _p(w_norm), _p(bias), _p(y), _p(saved_h),
                               _p(saved_inner), _p(w_norm_out), _p(ws), _nbytes(ws), _stream(stream)), "dora_forward")
 
 
-def dora_forward_fused(desc, x, W, A, B, m, w_norm, y, saved_h, saved_inner, w_norm_out, ws, stream=None) -> None:
-    _check(lib().dora_forward_fused(ctypes.byref(desc), _p(x), _p(W), _p(A), _p(B), _p(m), _p(w_norm), _p(y),
+def dora_forward_fused(desc, x, W, A, B, m, w_norm, bias, y, saved_h, saved_inner, w_norm_out, ws, stream=None) -> None:
+    _check(lib().dora_forward_fused(ctypes.byref(desc), _p(x), _p(W), _p(A), _p(B), _p(m), _p(w_norm), _p(bias), _p(y),
                                     _p(saved_h), _p(saved_inner), _p(w_norm_out), _p(ws), _nbytes(ws),
                                     _stream(stream)), "dora_forward_fused")
 

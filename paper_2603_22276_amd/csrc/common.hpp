@@ -76,6 +76,7 @@ struct GemmArgs {
     int ksplit;                // split of segment 0's K range (nseg must be 1 when > 1)
     int tag;                   // 0 or 1: selects a differently named (otherwise identical) kernel instance
     const float* colscale;     // EPI_COMPOSE: [N] fp32
+    const bf16_t* colbias;     // EPI_COMPOSE: [N] bf16 added to the scaled output, or nullptr
     void* c2;                  // second output [M, ldc] bf16 or nullptr: the unscaled accumulator (compose epilogue),
                                // alpha2 * accumulator (bf16 store epilogue)
     float alpha2;
@@ -116,8 +117,9 @@ hipError_t launch_sgemm_f32(const SgemmArgs& a, int trace_id, hipStream_t stream
 
 // ---- element-wise / reduction kernels -----------------------------------------------------------
 hipError_t launch_mag_scale(const float* m, const float* c, float eps, float* g, float* gm1, int d_out, hipStream_t st);
-hipError_t launch_compose_fwd(int dtype, const void* base, const void* lora, const float* g, const float* gm1, float s,
-                              void* out, int write_delta, void* inner, int64_t tokens, int d_out, hipStream_t st);
+hipError_t launch_compose_fwd(int dtype, const void* base, const void* lora, const float* g, const float* gm1,
+                              const void* bias, float s, void* out, int write_delta, void* inner, int64_t tokens,
+                              int d_out, hipStream_t st);
 int compose_bwd_slabs(int64_t tokens, int d_out, int dtype);
 hipError_t launch_compose_bwd(int dtype, const void* dy, const void* inner, const float* g, void* dz,
                               float* partial /* [slabs][d_out] or nullptr */, int64_t tokens, int d_out, hipStream_t st);

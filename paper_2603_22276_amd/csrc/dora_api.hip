@@ -414,7 +414,7 @@ dora_status dora_compose(const dora_desc* desc, const void* base, const void* lo
     if (st != DORA_OK) return st;
     DORA_REQ_PTR(base); DORA_REQ_PTR(lora); DORA_REQ_PTR(g); DORA_REQ_PTR(out);
     DORA_OPT_PTR(gm1); DORA_OPT_PTR(inner);
-    DORA_HIP(launch_compose_fwd(desc->dtype, base, lora, g, gm1, desc->s, out, write_delta, inner, desc->tokens,
+    DORA_HIP(launch_compose_fwd(desc->dtype, base, lora, g, gm1, nullptr, desc->s, out, write_delta, inner, desc->tokens,
                                 (int)desc->d_out, (hipStream_t)stream));
     return DORA_OK;
 }
@@ -452,14 +452,14 @@ dora_status dora_project(const dora_desc* desc, const void* x, const void* W, co
 }
 
 dora_status dora_forward(const dora_desc* desc, const void* x, const void* W, const void* A, const void* B,
-                         const float* m, const float* w_norm, void* y, void* saved_h, void* saved_inner,
+                         const float* m, const float* w_norm, const void* bias, void* y, void* saved_h, void* saved_inner,
                          float* w_norm_out, void* ws, size_t ws_bytes, void* stream)
 {
     dora_status st = check_desc(desc, true);
     if (st != DORA_OK) return st;
     DORA_REQ_PTR(W); DORA_REQ_PTR(A); DORA_REQ_PTR(B); DORA_REQ_PTR(m);
     if (desc->tokens > 0) { DORA_REQ_PTR(x); DORA_REQ_PTR(y); }
-    DORA_OPT_PTR(w_norm); DORA_OPT_PTR(saved_h); DORA_OPT_PTR(saved_inner); DORA_OPT_PTR(w_norm_out);
+    DORA_OPT_PTR(w_norm); DORA_OPT_PTR(bias); DORA_OPT_PTR(saved_h); DORA_OPT_PTR(saved_inner); DORA_OPT_PTR(w_norm_out);
     const bool need_norm = (w_norm == nullptr);
     Bump sizing(nullptr);
     FwdPlan p;
@@ -484,12 +484,13 @@ dora_status dora_forward(const dora_desc* desc, const void* x, const void* W, co
     void* h = saved_h ? saved_h : p.h;
     void* lora = saved_inner ? saved_inner : p.lora;
     if ((st = forward_contractions(desc, x, W, A, B, y, h, lora, s)) != DORA_OK) return st;
-    DORA_HIP(launch_compose_fwd(desc->dtype, y, lora, p.g, p.gm1, desc->s, y, 0, saved_inner, desc->tokens, d_out, s));
+    DORA_HIP(launch_compose_fwd(desc->dtype, y, lora, p.g, p.gm1, bias, desc->s, y, 0, saved_inner, desc->tokens, d_out,
+                                s));
     return DORA_OK;
 }
 
 dora_status dora_forward_fused(const dora_desc* desc, const void* x, const void* W, const void* A, const void* B,
-                               const float* m, const float* w_norm, void* y, void* saved_h, void* saved_inner,
+                               const float* m, const float* w_norm, const void* bias, void* y, void* saved_h, void* saved_inner,
                                float* w_norm_out, void* ws, size_t ws_bytes, void* stream)
 {
     dora_status st = check_desc(desc, true);
@@ -497,7 +498,7 @@ dora_status dora_forward_fused(const dora_desc* desc, const void* x, const void*
     if (desc->dtype != DORA_BF16) return DORA_ERR_DTYPE;
     DORA_REQ_PTR(W); DORA_REQ_PTR(A); DORA_REQ_PTR(B); DORA_REQ_PTR(m);
     if (desc->tokens > 0) { DORA_REQ_PTR(x); DORA_REQ_PTR(y); }
-    DORA_OPT_PTR(w_norm); DORA_OPT_PTR(saved_h); DORA_OPT_PTR(saved_inner); DORA_OPT_PTR(w_norm_out);
+    DORA_OPT_PTR(w_norm); DORA_OPT_PTR(bias); DORA_OPT_PTR(saved_h); DORA_OPT_PTR(saved_inner); DORA_OPT_PTR(w_norm_out);
     const bool need_norm = (w_norm == nullptr);
     Bump sizing(nullptr);
     FwdPlan p;
@@ -530,6 +531,7 @@ dora_status dora_forward_fused(const dora_desc* desc, const void* x, const void*
     GemmArgs g = bf16_args(true, true, T, d_out, segs, 2, 1.f, y, d_out, false, 0);
     g.epilogue = EPI_COMPOSE;
     g.colscale = p.g;
+    g.colbias = (const bf16_t*)bias;
     g.c2 = saved_inner;
     DORA_HIP(launch_gemm_bf16(g, DORA_K_GEMM_FUSED_FWD, s));
     return DORA_OK;
@@ -581,7 +583,7 @@ dora_status dora_backward(const dora_desc* desc, const void* dy, const void* x, 
             if ((st = forward_contractions(desc, x, W, A, B, p.dz, hbuf, p.inner, s)) != DORA_OK) return st;
             h = hbuf;
         }
-        DORA_HIP(launch_compose_fwd(dt, p.dz, p.inner, p.g, p.gm1, desc->s, nullptr, 0, p.inner, T, d_out, s));
+        DORA_HIP(launch_compose_fwd(dt, p.dz, p.inner, p.g, p.gm1, nullptr, desc->s, nullptr, 0, p.inner, T, d_out, s));
         inner = p.inner;
     } else if (T > 0 && need_h) {
         Seg s1{x, d_in, A, d_in, d_in};

@@ -153,6 +153,7 @@ template <typename T, int OUTMODE, bool INNER>
 __global__ __launch_bounds__(CW* CH) void compose_fwd_kernel(const T* base_, const T* lora_,  // out may alias base, inner may alias lora
                                                              
                                                               const float* __restrict__ g, const float* __restrict__ gm1,
+                                                              const T* __restrict__ bias,  // added to out = base + delta only; may be null
                                                               float s, T* out_, T* inner_, int64_t tokens, int d_out,
                                                               int rows_per_wg)
 {
@@ -161,12 +162,14 @@ __global__ __launch_bounds__(CW* CH) void compose_fwd_kernel(const T* base_, con
     constexpr int N = V::N;
     const int col = (blockIdx.x * CW + threadIdx.x) * N;
     if (col >= d_out) return;
-    float gv[N], g1[N];
+    float gv[N], g1[N], bv[N];
 #pragma unroll
     for (int i = 0; i < N; ++i) {
         gv[i] = g[col + i];
         g1[i] = gm1 ? gm1[col + i] : gv[i] - 1.0f;
+        bv[i] = 0.f;
     }
+    if (OUTMODE == 1 && bias) V::unpack(*reinterpret_cast<const raw_t*>(bias + col), bv);
     const int64_t row_begin = (int64_t)blockIdx.y * rows_per_wg;
     int64_t row_end = row_begin + rows_per_wg;
     if (row_end > tokens) row_end = tokens;
@@ -192,7 +195,7 @@ __global__ __launch_bounds__(CW* CH) void compose_fwd_kernel(const T* base_, con
                 for (int i = 0; i < N; ++i) {
                     float sl = s * lf[i];                        // canonical order: s*lora first, then g*(.)
                     float delta = fmaf(g1[i], bf[i], gv[i] * sl);
-                    of[i] = (OUTMODE == 2) ? delta : bf[i] + delta;
+                    of[i] = (OUTMODE == 2) ? delta : (bf[i] + delta) + bv[i];
                     inf[i] = sl + bf[i];
                 }
                 if (OUTMODE != 0) store_stream(out_ + rr * d_out + col, V::pack(of));
@@ -367,8 +370,9 @@ static int slab_rows(int preferred, int64_t tokens, int d_out, int dtype)
 }
 
 template <typename T>
-static hipError_t compose_fwd_t(const void* base, const void* lora, const float* g, const float* gm1, float s, void* out,
-                                int write_delta, void* inner, int64_t tokens, int d_out, hipStream_t st)
+static hipError_t compose_fwd_t(const void* base, const void* lora, const float* g, const float* gm1, const void* bias,
+                                float s, void* out, int write_delta, void* inner, int64_t tokens, int d_out,
+                                hipStream_t st)
 {
     constexpr int N = Vec<T>::N;
     int cpr = d_out / N;
@@ -380,7 +384,7 @@ static hipError_t compose_fwd_t(const void* base, const void* lora, const float*
     T* o = (T*)out;
     T* in = (T*)inner;
 #define DORA_LAUNCH_FWD(D, I) \
-    compose_fwd_kernel<T, D, I><<<grid, block, 0, st>>>(b, l, g, gm1, s, o, in, tokens, d_out, FWD_ROWS_PER_WG)
+    compose_fwd_kernel<T, D, I><<<grid, block, 0, st>>>(b, l, g, gm1, (const T*)bias, s, o, in, tokens, d_out, FWD_ROWS_PER_WG)
     if (!out) { DORA_LAUNCH_FWD(0, true); }
     else if (write_delta) { if (inner) DORA_LAUNCH_FWD(2, true); else DORA_LAUNCH_FWD(2, false); }
     else { if (inner) DORA_LAUNCH_FWD(1, true); else DORA_LAUNCH_FWD(1, false); }
@@ -388,13 +392,15 @@ static hipError_t compose_fwd_t(const void* base, const void* lora, const float*
     return hipGetLastError();
 }
 
-hipError_t launch_compose_fwd(int dtype, const void* base, const void* lora, const float* g, const float* gm1, float s,
-                              void* out, int write_delta, void* inner, int64_t tokens, int d_out, hipStream_t st)
+hipError_t launch_compose_fwd(int dtype, const void* base, const void* lora, const float* g, const float* gm1,
+                              const void* bias, float s, void* out, int write_delta, void* inner, int64_t tokens,
+                              int d_out, hipStream_t st)
 {
     if (tokens == 0 || d_out == 0) return hipSuccess;
     TraceScope ts(DORA_K_COMPOSE_FWD, st);
-    if (dtype == DORA_BF16) return compose_fwd_t<bf16_t>(base, lora, g, gm1, s, out, write_delta, inner, tokens, d_out, st);
-    return compose_fwd_t<float>(base, lora, g, gm1, s, out, write_delta, inner, tokens, d_out, st);
+    if (dtype == DORA_BF16)
+        return compose_fwd_t<bf16_t>(base, lora, g, gm1, bias, s, out, write_delta, inner, tokens, d_out, st);
+    return compose_fwd_t<float>(base, lora, g, gm1, bias, s, out, write_delta, inner, tokens, d_out, st);
 }
 
 static int compose_bwd_rows(int64_t tokens, int d_out, int dtype) { return slab_rows(64, tokens, d_out, dtype); }

@@ -105,14 +105,14 @@ class Module:
         D.dora_norm(self.desc, self.W, self.A, self.B, c, workspace(self.desc, D.PHASE_NORM))
         return c
 
-    def forward(self, w_norm=None, save=True, fused=False):
+    def forward(self, w_norm=None, save=True, fused=False, bias=None):
         cfg = self.cfg
         y = empty((cfg.tokens, cfg.d_out), cfg.dtype)
         h = empty((cfg.tokens, cfg.r), cfg.dtype) if save else None
         inner = empty((cfg.tokens, cfg.d_out), cfg.dtype) if save else None
         c = empty_f32(cfg.d_out)
         fn = D.dora_forward_fused if fused else D.dora_forward
-        fn(self.desc, self.x, self.W, self.A, self.B, self.m, w_norm, y, h, inner, c,
+        fn(self.desc, self.x, self.W, self.A, self.B, self.m, w_norm, bias, y, h, inner, c,
            workspace(self.desc, D.PHASE_FORWARD))
         return {"y": y, "h": h, "inner": inner, "c": c}
 

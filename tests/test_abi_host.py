@@ -83,8 +83,9 @@ def test_argument_errors_are_reported_before_any_launch():
         assert L.dora_norm(ctypes.byref(bad), FAKE, FAKE, FAKE, FAKE, FAKE, big, None) == 2
     assert L.dora_norm(ctypes.byref(desc(dtype=3)), FAKE, FAKE, FAKE, FAKE, FAKE, big, None) == 4
     # forward / backward / compose reject the same way
-    assert L.dora_forward(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, None, None, FAKE, None, None, None, FAKE, big, None) == 1
-    assert L.dora_forward(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, None, None, None, FAKE, 1024, None) == 5
+    assert L.dora_forward(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, None, None, None, FAKE, None, None, None, FAKE, big, None) == 1
+    assert L.dora_forward(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, None, None, None, FAKE, 1024, None) == 5
+    assert L.dora_forward(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE + 2, FAKE, None, None, None, FAKE, big, None) == 3
     assert L.dora_backward(ctypes.byref(d), None, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, None, FAKE, FAKE, FAKE,
                            FAKE, FAKE, big, None) == 1
     assert L.dora_compose(ctypes.byref(d), FAKE, FAKE, None, None, FAKE, 0, None, None) == 1

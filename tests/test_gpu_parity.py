@@ -372,3 +372,29 @@ def test_fused_forward_rejects_fp32():
     with pytest.raises(D.DoraError) as e:
         mod.forward(fused=True)
     assert e.value.status == 4
+
+
+# ----------------------------------------------------------------------------- bias of the base layer
+
+@pytest.mark.parametrize("cfg", [SMALL[0], SMALL[2], SMALL[5], SMALL[6]], ids=[IDS[0], IDS[2], IDS[5], IDS[6]])
+@pytest.mark.parametrize("fused", [False, True], ids=["compose_pass", "fused_epilogue"])
+def test_forward_with_bias(cfg, fused):
+    # App. A item 2: the frozen layer's bias is not part of the compose; y = base + delta + bias
+    if fused and cfg.dtype != "bf16":
+        pytest.skip("the K-concatenated forward is bf16 only")
+    mod = G.Module(cfg)
+    rng = np.random.default_rng(4242)
+    bias64 = rng.normal(size=cfg.d_out)
+    if cfg.dtype == "bf16":
+        stored = I.f32_to_bf16_bits(bias64.astype(np.float32))
+    else:
+        stored = bias64.astype(np.float32)
+    bias_dev = G.to_dev(stored)
+    ref = O.forward(**oracle_inputs(mod), bias=I.to_f64(stored))
+    out = mod.forward(fused=fused, bias=bias_dev)
+    tol = G.TOL[cfg.dtype]["tensor"]
+    G.assert_close("y", G.to_f64(out["y"]), ref["y"], tol)
+    G.assert_close("inner", G.to_f64(out["inner"]), ref["inner"], tol)
+    # the bias must really be there: without it the result is off by about |bias|
+    plain = O.forward(**oracle_inputs(mod))
+    assert G.rel_max(G.to_f64(out["y"]), plain["y"]) > 10 * tol

@@ -286,3 +286,23 @@ def test_stable_form_beats_naive_form_near_unity_g():
     e_naive = np.max(np.abs(naive - ref))
     assert e_stable <= 2.0 ** -8 * np.max(np.abs(ref))  # within bf16 rounding of the result
     assert e_naive > 3 * e_stable
+
+
+def test_bias_is_re_added_unscaled():
+    # App. A item 2: the base layer's bias is subtracted before the compose and re-added after, so the module
+    # output is x W'^T + bias with W' the adapted weight of Eq. (1) -- the bias is NOT multiplied by g.
+    rng = np.random.default_rng(77)
+    d_out, d_in, r, T = 12, 10, 3, 5
+    W, A, B = rng.normal(size=(d_out, d_in)), rng.normal(size=(r, d_in)), rng.normal(size=(d_out, r))
+    x, bias = rng.normal(size=(T, d_in)), rng.normal(size=d_out)
+    m = np.abs(rng.normal(size=d_out)) + 0.5
+    s, eps = 0.7, 1e-12
+    f = O.forward(x, W, A, B, m, s, eps, bias=bias)
+    Wp = O.adapted_weight(W, A, B, m, s, eps)
+    np.testing.assert_allclose(f["y"], x @ Wp.T + bias[None, :], rtol=1e-12, atol=1e-12)
+    g = f["g"]
+    assert np.max(np.abs(g - 1.0)) > 0.05  # scaling the bias by g would be visible
+    wrong = x @ Wp.T + (g * bias)[None, :]
+    assert np.max(np.abs(f["y"] - wrong)) > 1e-3
+    # inner is the bias-free pre-scale activation
+    np.testing.assert_allclose(f["inner"], x @ (W + s * B @ A).T, rtol=1e-12, atol=1e-12)
