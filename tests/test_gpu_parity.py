@@ -291,6 +291,33 @@ def test_forward_backward(cfg):
         assert torch.equal(gf[k].view(torch.uint8), ref[k].view(torch.uint8)), k
 
 
+MINIMAL = [
+    cfg_bf16("bf16_minimum", 8, 8, 8, 1, sigma_B=2e-2, seed=31),       # the smallest shapes the ABI accepts
+    cfg_f32("f32_minimum", 4, 4, 4, 1, seed=32),
+    cfg_bf16("bf16_one_token_wide", 8, 1032, 8, 1, sigma_B=2e-2, seed=33),
+    cfg_bf16("bf16_rank_over_dims", 72, 40, 136, 65, sigma_B=2e-2, seed=34),   # r larger than d_in and d_out
+]
+
+
+@pytest.mark.parametrize("cfg", MINIMAL, ids=[c.name for c in MINIMAL])
+def test_forward_backward_at_degenerate_sizes(cfg):
+    mod = G.Module(cfg)
+    oi = oracle_inputs(mod)
+    f = O.forward(**oi)
+    tol = G.TOL[cfg.dtype]["tensor"]
+    out = mod.forward()
+    G.assert_norm_close(G.to_f64(out["c"]), f["c"], G.TOL[cfg.dtype]["norm"])
+    for k in ("y", "inner", "h"):
+        G.assert_close(k, G.to_f64(out[k]), f[k], tol)
+    if cfg.dtype == "bf16":
+        fused = mod.forward(fused=True)
+        G.assert_close("y [fused]", G.to_f64(fused["y"]), f["y"], tol)
+    b = O.backward(mod.f64("dy"), **oi)
+    grads = mod.backward()
+    for k in ("dx", "dA", "dB", "dm"):
+        G.assert_close(k, G.to_f64(grads[k]), b[k], tol)
+
+
 def test_initial_state_is_identity():
     # B = 0 and m = ||W||_row (DoRA's initialisation): y equals the base projection
     cfg = cfg_bf16("init", 520, 392, 40, 300, seed=9)
