@@ -282,7 +282,7 @@ __global__ __launch_bounds__(CW* CH) void compose_bwd_kernel(const T* __restrict
 }
 
 // Second stage: dm[j] = (sum over slabs, in slab order) / max(c[j], eps).
-constexpr int DMF_W = 64, DMF_H = 4;
+constexpr int DMF_W = 32, DMF_H = 32;
 __global__ __launch_bounds__(DMF_W* DMF_H) void dm_final_kernel(const float* __restrict__ partial, int slabs,
                                                                  const float* __restrict__ c, float eps,
                                                                  float* __restrict__ dm, int d_out)
