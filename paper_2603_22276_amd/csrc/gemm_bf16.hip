@@ -447,8 +447,9 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
         //     N side, step u+2:  first half behind barrier(u), second half in the burst after it,
         //     M side, step u+3:  the two bursts after that,
         // N side before M side, so that waiting for all but the last M-side step's loads means the N-side
-        // ones have landed (loads complete in order).  The N-side loads have most of a K step to land,
-        // the M-side ones that plus a whole step.
+        // ones have landed (loads complete in order).  The N-side loads have about one K step to land (they
+        // are needed at barrier(u+1)), the M-side ones about one and a half (barrier(u+2)); with two slots
+        // for both operands every load of a step would have to be issued and to land within one step.
         constexpr int NM = MT * NT, NF = MT + NT;
         constexpr int HA = T::NLA / 2, HB = T::NLB / 2;
         static_assert(KSTEPS == 4 && NF <= NM && STAGES == 2, "burst schedule assumptions");
