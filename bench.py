@@ -254,6 +254,19 @@ def main():
 
     ms_untraced = timed(step)
 
+    # the same step captured once in a HIP graph and replayed: what is left of the gaps between the sixteen launches
+    ms_graph = None
+    try:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        for _ in range(2):
+            graph.replay()
+        ms_graph = timed(graph.replay)
+        del graph
+    except Exception as exc:  # pragma: no cover - informational figure only
+        print(f"bench.py: graph replay not measured ({exc})", file=sys.stderr)
+
     # the other forward path (compose folded into the GEMM epilogue when the default is timed, and the
     # other way round), same backward, no event pairs: reported beside `value`, not instead of it
     other_fwd = D.dora_forward if args.fused_forward else D.dora_forward_fused
@@ -338,6 +351,7 @@ def main():
         "hbm_frac_compose_bwd": next(k["frac"] for k in kernels if k["kernel"] == "compose_bwd"),
         "ms_per_step_without_event_pairs": ms_untraced,
         "ms_per_step_with_every_kernel_bracketed": ms_all_events,
+        "ms_per_step_graph_replay": ms_graph,
         "other_forward_path": {"forward_path": "base, lora, compose pass" if args.fused_forward else "fused epilogue",
                                "ms_per_step_without_event_pairs": ms_other, "tokens_per_s": T / (ms_other * 1e-3)},
         "sustained_on_this_card": sustained,
