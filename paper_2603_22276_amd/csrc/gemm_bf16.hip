@@ -698,18 +698,8 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
     constexpr int ROWS_PER_PASS = 64 / CHUNKS_PER_ROW;
     char* stg = smem + wave * T::EPI_BYTES_PER_WAVE;
     // EPI_COMPOSE: pass 0 writes colscale[n] * acc to C (y = g (.) inner), pass 1 writes acc to C2 (inner)
-    float4 cs[NT][4];
-    uint2 cbias[NT][4];   // four bf16 of the bias per column group (zeros without a bias)
-    if (EPI == EPI_COMPOSE) {
-#pragma unroll
-        for (int j = 0; j < NT; ++j)
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const int ng = n0 + wn0 + j * 32 + b * 8 + lh * 4;
-                cs[j][b] = (ng < p.N) ? *reinterpret_cast<const float4*>(p.colscale + ng) : make_float4(0.f, 0.f, 0.f, 0.f);
-                cbias[j][b] = (p.colbias && ng < p.N) ? *reinterpret_cast<const uint2*>(p.colbias + ng) : make_uint2(0u, 0u);
-            }
-    }
+    // (the per-column scale and bias are re-read for every 32-row band: sixteen float4 per lane kept
+    // across the whole epilogue would not fit beside 256 accumulators)
     // EPI_STORE_BF16 with a second output: pass 1 writes alpha2 * acc to C2
     const int npass = ((EPI == EPI_COMPOSE || EPI == EPI_STORE_BF16) && p.c2 != nullptr) ? 2 : 1;
     for (int pass = 0; pass < npass; ++pass) {
@@ -725,8 +715,13 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
                 const int col = j * 32 + b * 8 + lh * 4;
                 float v0, v1, v2, v3;
                 if (EPI == EPI_COMPOSE) {
-                    const float4 g4 = (pass == 0) ? cs[j][b] : make_float4(1.f, 1.f, 1.f, 1.f);
-                    const uint2 b4 = (pass == 0) ? cbias[j][b] : make_uint2(0u, 0u);
+                    float4 g4 = make_float4(1.f, 1.f, 1.f, 1.f);
+                    uint2 b4 = make_uint2(0u, 0u);
+                    if (pass == 0) {
+                        const int ng = n0 + wn0 + col;
+                        g4 = (ng < p.N) ? *reinterpret_cast<const float4*>(p.colscale + ng) : make_float4(0.f, 0.f, 0.f, 0.f);
+                        if (p.colbias && ng < p.N) b4 = *reinterpret_cast<const uint2*>(p.colbias + ng);
+                    }
                     v0 = fmaf(g4.x, acc[i][j][b * 4 + 0], bf16_lo(b4.x)); v1 = fmaf(g4.y, acc[i][j][b * 4 + 1], bf16_hi(b4.x));
                     v2 = fmaf(g4.z, acc[i][j][b * 4 + 2], bf16_lo(b4.y)); v3 = fmaf(g4.w, acc[i][j][b * 4 + 3], bf16_hi(b4.y));
                 } else {
