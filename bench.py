@@ -181,8 +181,7 @@ def main():
     import torch
     from paper_2603_22276_amd import binding as D
     from paper_2603_22276_amd import inputs as I
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    import gpu_util as G
+    from paper_2603_22276_amd import device as G
 
     cfg = {"C2": I.C2, "C3": I.C3}[args.config]
     inp = I.make_inputs(cfg)

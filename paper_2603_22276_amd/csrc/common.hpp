@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "../../include/dora.h"
+#include "../../include/dora_measure.h"
 
 namespace dora {
 
@@ -35,7 +36,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_hw_t));
 }
 
-// ---- kernel timing hook (see dora_trace_* in dora.h) ------------------------------------------
+// ---- kernel timing hook (see dora_trace_* in dora_measure.h) ------------------------------------------
 void trace_begin(int kernel_id, hipStream_t stream);
 void trace_end(int kernel_id, hipStream_t stream);
 

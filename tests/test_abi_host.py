@@ -13,7 +13,7 @@ FAKE = 0x10000  # a 256-byte aligned, never dereferenced "device pointer"
 
 
 def header_functions():
-    text = open(os.path.join(ROOT, "include", "dora.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", h)).read() for h in sorted(os.listdir(os.path.join(ROOT, "include"))))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(dora_[a-z_]+)\s*\(", text)))
 

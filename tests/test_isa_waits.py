@@ -124,7 +124,8 @@ def test_no_mfma_reads_a_fragment_before_its_wait(tmp_path):
     csrc = os.path.join(ROOT, "paper_2603_22276_amd", "csrc")
     for f in os.listdir(csrc):
         shutil.copy(os.path.join(csrc, f), stage / f)
-    shutil.copy(os.path.join(ROOT, "include", "dora.h"), tmp_path / "include" / "dora.h")
+    for f in os.listdir(os.path.join(ROOT, "include")):
+        shutil.copy(os.path.join(ROOT, "include", f), tmp_path / "include" / f)
     asm = tmp_path / "gemm.s"
     cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-S", "--cuda-device-only", "-o", str(asm), str(stage / "gemm_bf16.hip")]
