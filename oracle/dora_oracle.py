@@ -21,10 +21,10 @@ What is defined here, and from where:
 * `backward` / `grad_*`                - Sec. 3.2 and App. C item 2: gradients of
   the compose, chained through the three linear maps, with the norm held
   constant (Sec. 2.2 last paragraph; App. A item 2 "detached").
-* `factored_norm_terms`, `assemble_norm` - Algorithm 1 and Eq. (2)-(5), step by
-  step in the paper's order.  Not used to judge the HIP norm (the dense
-  definition is); kept so the three terms can be checked one by one and so the
-  identity itself is pinned against the dense form.
+* `factored_norm_terms`, `assemble_norm` - the terms of Eq. (2), each from its
+  definition (Eq. 3, Eq. 4), and the assembly of Eq. (5).  Not used to judge the
+  HIP norm (the dense definition is); kept so the three terms can be checked one
+  by one and so the identity itself is pinned against the dense form.
 
 Pins (tests/test_oracle_pins.py): B=0 / s=0 special cases, the r=1 closed form,
 orthonormal-A and W=0 cases, homogeneity, Cauchy-Schwarz on the cross term,
@@ -184,26 +184,26 @@ def backward(dy, x, W, A, B, m, s, eps, c=None) -> Dict[str, np.ndarray]:
 
 # --------------------------------------------------------------------------- Algorithm 1 (factored form)
 
-def factored_norm_terms(W, A, B, chunk: Optional[int] = None) -> Dict[str, np.ndarray]:
-    """Algorithm 1, the loop over d_in chunks, in the paper's order.
+def factored_norm_terms(W, A, B, cols=None) -> Dict[str, np.ndarray]:
+    """The terms of Eq. (2), each written from its own definition (Eq. 3, Eq. 4):
 
-    Returns base_sq [d_out], cross [d_out], G [r, r] and ba_sq [d_out].
+      base_sq[j] = ||W_j||^2                      = sum_k W[j,k]^2
+      cross[j]   = <W_j, (B A)_j>                 = sum_l B[j,l] (W A^T)[j,l]         (Eq. 3)
+      G          = A A^T                                                              (Eq. 4)
+      ba_sq[j]   = ||(B A)_j||^2 = B_j G B_j^T    = sum_l sum_p B[j,l] G[l,p] B[j,p]
+
+    `cols` restricts W and A to a subset of the d_in columns.  Every term is a sum over columns (ba_sq
+    is linear in G), so the values over the blocks of any partition of d_in add up to the values over
+    all columns: the property Algorithm 1's chunk loop rests on.
     """
     W, A, B = _f64(W), _f64(A), _f64(B)
-    d_out, d_in = W.shape
-    r = A.shape[0]
-    cs = d_in if chunk is None else int(chunk)
-    base_sq = np.zeros(d_out, F64)
-    cross = np.zeros(d_out, F64)
-    G = np.zeros((r, r), F64)
-    for c0 in range(0, d_in, cs):
-        W_c = W[:, c0:c0 + cs]
-        A_c = A[:, c0:c0 + cs]
-        base_sq += np.sum(W_c ** 2, axis=1)
-        G += A_c @ A_c.T
-        U_c = W_c @ A_c.T
-        cross += np.sum(B * U_c, axis=1)
-    ba_sq = np.sum((B @ G) * B, axis=1)
+    if cols is not None:
+        W, A = W[:, cols], A[:, cols]
+    base_sq = np.einsum("jk,jk->j", W, W)
+    U = W @ A.T                                   # [d_out, r]
+    cross = np.einsum("jl,jl->j", B, U)
+    G = A @ A.T                                   # [r, r]
+    ba_sq = np.einsum("jl,lp,jp->j", B, G, B)
     return {"base_sq": base_sq, "cross": cross, "G": G, "ba_sq": ba_sq}
 
 
@@ -216,11 +216,22 @@ def assemble_norm(base_sq, cross, ba_sq, s) -> np.ndarray:
 
 
 def factored_row_norm(W, A, B, s, chunk: Optional[int] = None) -> np.ndarray:
+    """Eq. (5) from the factored terms; with `chunk`, the column sums are accumulated block by block
+    over d_in (Algorithm 1's memory-bounded schedule) and ba_sq comes from the accumulated G."""
     if F64(s) == 0.0:  # scale-is-zero fast path of Algorithm 1's notes
         W = _f64(W)
         return np.sqrt(np.sum(W * W, axis=1))
-    t = factored_norm_terms(W, A, B, chunk)
-    return assemble_norm(t["base_sq"], t["cross"], t["ba_sq"], s)
+    if chunk is None:
+        t = factored_norm_terms(W, A, B)
+        return assemble_norm(t["base_sq"], t["cross"], t["ba_sq"], s)
+    B = _f64(B)
+    d_in = _f64(W).shape[1]
+    blocks = [factored_norm_terms(W, A, B, slice(c0, c0 + int(chunk))) for c0 in range(0, d_in, int(chunk))]
+    base_sq = sum(b["base_sq"] for b in blocks)
+    cross = sum(b["cross"] for b in blocks)
+    G = sum(b["G"] for b in blocks)
+    ba_sq = np.einsum("jl,lp,jp->j", B, G, B)
+    return assemble_norm(base_sq, cross, ba_sq, s)
 
 
 def chunk_size(budget_bytes: int, d_out: int, d_in: int) -> int:

@@ -124,6 +124,25 @@ def test_factored_equals_dense_brute_force(seed):
     np.testing.assert_allclose(dense, np.linalg.norm(W + s * B @ A, axis=1), rtol=1e-13)
 
 
+def test_factored_terms_add_over_any_partition_of_the_columns():
+    # every term is a sum over d_in (ba_sq is linear in G): over the blocks of a partition they add up
+    # to the whole, which is what lets Algorithm 1 walk d_in in chunks
+    rng = np.random.default_rng(77)
+    W, A, B = rng.standard_normal((6, 11)), rng.standard_normal((3, 11)), rng.standard_normal((6, 3))
+    whole = O.factored_norm_terms(W, A, B)
+    perm = rng.permutation(11)
+    parts = [perm[:2], perm[2:7], perm[7:]]
+    blocks = [O.factored_norm_terms(W, A, B, p) for p in parts]
+    for k in ("base_sq", "cross", "G", "ba_sq"):
+        np.testing.assert_allclose(sum(b[k] for b in blocks), whole[k], rtol=1e-13, atol=1e-13)
+    # each term against its own brute-force definition
+    BA = B @ A
+    np.testing.assert_allclose(whole["base_sq"], [sum(v * v for v in row) for row in W], rtol=1e-14)
+    np.testing.assert_allclose(whole["cross"], [float(W[j] @ BA[j]) for j in range(6)], rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(whole["ba_sq"], [float(BA[j] @ BA[j]) for j in range(6)], rtol=1e-13)
+    np.testing.assert_allclose(whole["G"], [[float(A[l] @ A[p]) for p in range(3)] for l in range(3)], rtol=1e-14)
+
+
 def test_assembly_clamp_and_nan():
     # negative radicand (rounding artefact) clamps to 0; NaN propagates (App. C item 3)
     out = O.assemble_norm(np.array([1.0, np.nan, 4.0]), np.array([-1.0, 0.0, 0.0]), np.array([0.0, 0.0, 0.0]), 1.0)
@@ -224,6 +243,33 @@ def test_negative_control_norm_not_detached_differs():
         assert np.max(np.abs(fd - b[name])) <= 1e-7 * np.max(np.abs(fd)), name
 
 
+def test_compose_gradients_match_finite_differences_of_the_compose():
+    # L(base, lora, g) = sum dy * (base + delta(base, lora, g)) with delta from the compose equation
+    # (App. A item 1): grad_compose must return dL/dlora, dL/dbase and, through g = m / max(c, eps)
+    # with c constant, dL/dm = (dL/dg) / max(c, eps).  A wrong factor (s missing, g-1 in place of g,
+    # the wrong reduction axis) shows up here.
+    rng = np.random.default_rng(11)
+    T, n, s = 4, 5, 0.7
+    dy = rng.standard_normal((T, n)); base = rng.standard_normal((T, n)); lora = rng.standard_normal((T, n))
+    c = np.abs(rng.standard_normal(n)) + 1.0
+    m = c * (1 + 1e-2 * rng.standard_normal(n))
+    eps = 1e-12
+
+    def loss():
+        g = m / np.maximum(c, eps)
+        return float(np.sum(dy * (base + O.compose_delta(base, lora, g, s))))
+
+    g = m / np.maximum(c, eps)
+    inner = s * lora + base
+    d_lora, d_base, dm = O.grad_compose(dy, inner, g, c, s, eps)
+    for name, arr, got in (("d_lora", lora, d_lora), ("d_base", base, d_base), ("dm", m, dm)):
+        fd = _fd(loss, arr)
+        assert np.max(np.abs(fd - got)) <= 1e-8 * np.max(np.abs(fd)), name
+    # compose_delta itself against the printed equation, element by element
+    j, t = 2, 1
+    assert O.compose_delta(base, lora, g, s)[t, j] == pytest.approx(g[j] * (s * lora[t, j]) + (g[j] - 1) * base[t, j], rel=1e-14)
+
+
 def test_compose_gradients_elementwise():
     # Sec. 3.2: d_lora = g s dy, d_base (via delta) = (g-1) dy; with y = base + delta, base gets g dy.
     rng = np.random.default_rng(10)
@@ -258,6 +304,11 @@ def test_table1_concrete_numbers():
     assert round(4 * (d * r + r * r) / MiB, 1) == vals["U_plus_G"]
     assert round(O.theory_memory_ratio(d, d, r), 1) == vals["reduction"]
     assert O.chunk_size(256 * 2 ** 20, d, d) == vals["chunk_at_256MiB_d8192"]
+    # the align-to-64 branch (App. B "Chunk alignment"), by hand: 256 MiB / (4 B x 27648 rows) = 2427.26 columns,
+    # below d_in = 5120, so floor(2427 / 64) x 64 = 37 x 64 = 2368
+    assert O.chunk_size(256 * 2 ** 20, 27648, 5120) == 2368
+    assert O.chunk_size(256 * 2 ** 20, 27648, 2000) == 2000      # whole d_in fits: no alignment applied
+    assert O.chunk_size(4 * 100 * 10, 100, 5120) == 64           # never below one aligned block
     assert 4 * r * r / MiB == vals["gram_bytes_r512"]
 
 
