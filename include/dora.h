@@ -76,6 +76,24 @@ dora_status dora_norm(const dora_desc* desc, const void* W, const void* A, const
                       float* w_norm, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * dora_norm for callers that cannot allocate or size a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): same result as dora_norm, bit for bit, with
+ * the scratch taken from a fixed array inside the library instead of `ws`.  Calls no hipMalloc,
+ * hipFree or other allocating routine.
+ *   - The array is dora_norm_static_max_bytes() = 16 MiB of device memory per GPU the library runs
+ *     on, held until the process ends.  A shape whose dora_workspace_bytes(desc, DORA_PHASE_NORM)
+ *     exceeds it is rejected with DORA_ERR_WORKSPACE before anything is enqueued (all five workload
+ *     shapes at r <= 512 fit; r = 768 does not).
+ *   - All calls on one GPU share that one array: two calls that overlap in time on the same GPU (two
+ *     streams, two threads) race.  Calls ordered on one stream are safe; nothing needs clearing between
+ *     them because each launch overwrites in full what the next one reads.
+ *   - The first call on a device looks up the array's address there (host-side, thread-safe).
+ */
+size_t dora_norm_static_max_bytes(void);
+dora_status dora_norm_static(const dora_desc* desc, const void* W, const void* A, const void* B,
+                             float* w_norm, void* stream);
+
+/*
  * Cached base term (Sec. 2.3: W is frozen, so the rank-independent term of Eq. 2 can be
  * computed once and kept in a [d_out] buffer).
  *   dora_base_sq     : base_sq[j] = sum_k W[j,k]^2, fp32 accumulation of the exact products.

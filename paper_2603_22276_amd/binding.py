@@ -19,7 +19,7 @@ PHASE_NORM, PHASE_FORWARD, PHASE_BACKWARD, PHASE_BACKWARD_RECOMPUTE, PHASE_COMPO
 K_COUNT = 19
 
 EXPORTS = (
-    "dora_workspace_bytes", "dora_norm", "dora_base_sq", "dora_norm_cached", "dora_mag_scale", "dora_compose", "dora_compose_backward",
+    "dora_workspace_bytes", "dora_norm", "dora_norm_static", "dora_norm_static_max_bytes", "dora_base_sq", "dora_norm_cached", "dora_mag_scale", "dora_compose", "dora_compose_backward",
     "dora_project", "dora_forward", "dora_forward_fused", "dora_backward", "dora_status_str",
     "dora_probe_copy", "dora_probe_mfma",
     "dora_trace_enable", "dora_trace_select", "dora_trace_reset", "dora_trace_collect", "dora_trace_get", "dora_trace_name",
@@ -54,6 +54,9 @@ def lib() -> ctypes.CDLL:
         L.dora_workspace_bytes.argtypes = [dp, ctypes.c_int]
         L.dora_workspace_bytes.restype = sz
         L.dora_norm.argtypes = [dp, vp, vp, vp, fp, vp, sz, vp]
+        L.dora_norm_static.argtypes = [dp, vp, vp, vp, fp, vp]
+        L.dora_norm_static_max_bytes.argtypes = []
+        L.dora_norm_static_max_bytes.restype = sz
         L.dora_base_sq.argtypes = [dp, vp, fp, vp]
         L.dora_norm_cached.argtypes = [dp, fp, vp, vp, vp, fp, vp, sz, vp]
         L.dora_mag_scale.argtypes = [dp, fp, fp, fp, fp, vp]
@@ -65,7 +68,7 @@ def lib() -> ctypes.CDLL:
         L.dora_backward.argtypes = [dp, vp, vp, vp, vp, vp, fp, fp, vp, vp, vp, fp, fp, fp, vp, sz, vp]
         L.dora_probe_copy.argtypes = [vp, vp, sz, vp]
         L.dora_probe_mfma.argtypes = [fp, ctypes.c_int, ctypes.c_int, vp]
-        for f in (L.dora_probe_copy, L.dora_probe_mfma, L.dora_norm, L.dora_base_sq, L.dora_norm_cached, L.dora_mag_scale, L.dora_compose, L.dora_compose_backward, L.dora_project, L.dora_forward, L.dora_forward_fused,
+        for f in (L.dora_probe_copy, L.dora_probe_mfma, L.dora_norm, L.dora_norm_static, L.dora_base_sq, L.dora_norm_cached, L.dora_mag_scale, L.dora_compose, L.dora_compose_backward, L.dora_project, L.dora_forward, L.dora_forward_fused,
                   L.dora_backward, L.dora_trace_collect, L.dora_trace_get):
             f.restype = ctypes.c_int
         L.dora_status_str.argtypes = [ctypes.c_int]
@@ -130,6 +133,14 @@ def dora_workspace_bytes(desc: dora_desc, phase: int) -> int:
 def dora_norm(desc, W, A, B, w_norm, ws, stream=None) -> None:
     _check(lib().dora_norm(ctypes.byref(desc), _p(W), _p(A), _p(B), _p(w_norm), _p(ws), _nbytes(ws), _stream(stream)),
            "dora_norm")
+
+
+def dora_norm_static(desc, W, A, B, w_norm, stream=None) -> None:
+    _check(lib().dora_norm_static(ctypes.byref(desc), _p(W), _p(A), _p(B), _p(w_norm), _stream(stream)), "dora_norm_static")
+
+
+def dora_norm_static_max_bytes() -> int:
+    return int(lib().dora_norm_static_max_bytes())
 
 
 def dora_base_sq(desc, W, base_sq, stream=None) -> None:

@@ -3,11 +3,38 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
 #include <vector>
 
 #include "common.hpp"
 
+// Scratch of the entry point that allocates nothing (dora_norm_static): one file-scope device array,
+// held by every GPU the library runs on until the process ends.  In host code the array's name is only
+// a stand-in; the device address is looked up once per device and used from then on.
+#define DORA_STATIC_SCRATCH_BYTES (16u << 20)
+static __device__ __align__(256) unsigned char scratch[DORA_STATIC_SCRATCH_BYTES];
+
 namespace dora {
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[MAX_DEVICES];  // per device: address of that device's copy of `scratch`
+
+// Device address of the current device's scratch array (nullptr on failure).
+void* static_scratch_ptr()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
 
 // ------------------------------------------------------------------------------------------------
 // kernel timing (dora_trace_*)
@@ -362,6 +389,27 @@ dora_status dora_norm(const dora_desc* desc, const void* W, const void* A, const
     plan_norm(desc, sizing, n);
     if ((st = check_ws(ws, ws_bytes, sizing.off)) != DORA_OK) return st;
     Bump b(ws);
+    plan_norm(desc, b, n);
+    return norm_impl(desc, W, A, B, w_norm, n, (hipStream_t)stream);
+}
+
+size_t dora_norm_static_max_bytes(void) { return DORA_STATIC_SCRATCH_BYTES; }
+
+dora_status dora_norm_static(const dora_desc* desc, const void* W, const void* A, const void* B, float* w_norm,
+                             void* stream)
+{
+    dora_status st = check_desc(desc, true);
+    if (st != DORA_OK) return st;
+    DORA_REQ_PTR(W); DORA_REQ_PTR(A); DORA_REQ_PTR(B); DORA_REQ_PTR(w_norm);
+    Bump sizing(nullptr);
+    NormPlan n;
+    plan_norm(desc, sizing, n);
+    if (sizing.off > DORA_STATIC_SCRATCH_BYTES) return DORA_ERR_WORKSPACE;  // shape beyond the static scratch
+    void* ptr = static_scratch_ptr();
+    if (!ptr) return DORA_ERR_HIP;
+    // every partial the norm kernels read back is written in full by the launch before it, so nothing
+    // left in the array by an earlier call (of any shape) needs clearing
+    Bump b(ptr);
     plan_norm(desc, b, n);
     return norm_impl(desc, W, A, B, w_norm, n, (hipStream_t)stream);
 }
