@@ -1,19 +1,29 @@
 #!/usr/bin/env python3
 """Benchmark of the DoRA module hot path on one MI355X.
 
-A "step" is one pass of the whole path over one batch of synthetic input: dora_forward (factored
-norm, magnitude scale, the three contractions, compose, saving h / inner / w_norm) followed by
-dora_backward (compose backward with the fused dm reduction, dh, dx, dA, dB).  The workload is the
-headline configuration: d_out = d_in = 8192, r = 384, tokens = 8192, bf16 storage with fp32
-accumulation.  Inputs are resident in HBM before the timed region starts.
+A "step" is one pass of the whole path over one batch of synthetic input, inputs resident in HBM before
+the timed region starts.  What the pass is depends on the workload (--config):
 
-Prints ONE JSON line: tokens/s for the step, a roofline object for the dominant kernel (duration
-measured with HIP events recorded by the library on the launch stream during the timed steps), the
-same figures for every other kernel, and the fp64 CPU oracle timed on a bounded sample.
+  C1  fp32, 256 x 512, r 16, 64 tokens: forward (factored norm inside).  Launch-latency bound.
+  C2  bf16, 4096 x 4096, r 384, 4096 tokens: forward (norm + contractions + compose).
+  C3  bf16, 8192 x 8192, r 384, 8192 tokens (the headline, default): forward saving h / inner / w_norm,
+      then backward (compose backward with the fused dm reduction, dh, dx, dA, dB).
+  C4  bf16 MLP pair, up 5120 -> 27648 and down 27648 -> 5120, r 384, 8192 tokens: forward of both modules
+      keeping nothing, then backward of both in reverse order with everything recomputed (norm, h, inner):
+      the gradient-checkpointing pattern.  tokens/s = 8192 / (t_up + t_down).
+  C5  bf16 decoder-layer sweep, 8B-class shapes: seven adapted modules x 32 layers, all 224 resident,
+      forward in order then recompute + backward in reverse order, at r = 64, 384 and 768; 4096 tokens.
+      Reports aggregate tokens/s (4096 / time of one sweep) and peak device memory per rank.
+
+Prints ONE JSON line: tokens/s of the step, per-step HIP-event timing (median, p10, p90), a roofline object
+for the dominant kernel (durations from HIP events the library records on the launch stream inside the timed
+steps), the same figures for every other kernel, and the fp64 CPU oracle timed on a bounded sample.
 """
 from __future__ import annotations
 
 import argparse
+import glob
+import hashlib
 import json
 import os
 import sys
@@ -22,13 +32,22 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
-PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_FP32_TFLOPS = 157.3    # MI355X fp32 vector ALU (the fp32 configuration runs on the VALU)
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+HBM_BOUND = {"compose_fwd", "compose_bwd", "mag_scale"}
+K_BASE, K_DX, K_FUSED = 6, 13, 18
+N_KERNEL_IDS = 19
+METRIC_FMT = "DoRA {phase} tokens/s at d_in={d_in} r={r} {dtype}; %MFMA and %HBM peak"
 
 
-def kernel_work(cfg):
-    """Algorithmic work per launch of each kernel: (flops, bytes), every operand touched once."""
-    T, do, di, r, e = cfg.tokens, cfg.d_out, cfg.d_in, cfg.r, 2
+def kernel_work(cfg, inner_saved=True):
+    """Algorithmic work per launch of each kernel: (flops, bytes), every operand touched once.  The forward
+    compose pass reads base and lora and writes y and, when it is kept for the backward, inner (4 tensors);
+    without the saved inner, and in the recompute that writes inner alone, it moves 3."""
+    T, do, di, r = cfg.tokens, cfg.d_out, cfg.d_in, cfg.r
+    e = 2 if cfg.dtype == "bf16" else 4
     return {
         "norm_cross_WAt": (2.0 * do * di * (r + 1), e * (do * di + r * di + do * r)),
         "gram_AAt": (2.0 * r * r * di, e * r * di),
@@ -39,7 +58,7 @@ def kernel_work(cfg):
         "gemm_base_xWt": (2.0 * T * do * di, e * (T * di + do * di + T * do)),
         "gemm_h_xAt": (2.0 * T * r * di, e * (T * di + r * di + T * r)),
         "gemm_lora_hBt": (2.0 * T * do * r, e * (T * r + do * r + T * do)),
-        "compose_fwd": (6.0 * T * do, e * 4.0 * T * do),       # reads base, lora; writes y, inner
+        "compose_fwd": (6.0 * T * do, e * (4.0 if inner_saved else 3.0) * T * do),
         "compose_bwd": (3.0 * T * do, e * 3.0 * T * do),       # reads dy, inner; writes dz
         "dm_final": (0.0, 0.0),
         "gemm_dh_dzB": (2.0 * T * r * do, e * (T * do + do * r + T * r)),
@@ -50,62 +69,283 @@ def kernel_work(cfg):
     }
 
 
-HBM_BOUND = {"compose_fwd", "compose_bwd", "mag_scale"}
+def kernel_sources_sha256():
+    """Hash of the kernel sources: counter summaries under profiles/ record the one they were taken at."""
+    h = hashlib.sha256()
+    for p in sorted(glob.glob(os.path.join(ROOT, "paper_2603_22276_amd", "csrc", "*"))):
+        h.update(os.path.basename(p).encode())
+        h.update(open(p, "rb").read())
+    return h.hexdigest()[:16]
 
 
 def hbm_traffic(workload, kernel):
-    """HBM bytes per launch of `kernel` as measured by the FETCH_SIZE / WRITE_SIZE counter passes whose
-    summary is kept under profiles/ (rocprofv3 cannot run inside this process); None if not recorded."""
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    """HBM-side bytes per launch of `kernel` from the FETCH_SIZE / WRITE_SIZE counter passes whose summary
+    is kept under profiles/ (rocprofv3 cannot run inside this process).  Returns (bytes or None, info):
+    the figure is withheld when the summary was taken at other kernel sources than the ones present."""
+    rel = f"profiles/hbm_traffic_{workload}.txt"
+    path = os.path.join(ROOT, rel)
+    info = {"source": rel, "counters": "FETCH_SIZE x calibrated factor + WRITE_SIZE x calibrated factor, per launch",
+            "measured_in_this_run": False}
     if not os.path.exists(path):
-        return None
+        info["note"] = "no counter summary for this workload"
+        return None, info
+    value, taken_at, commit = None, None, None
     for line in open(path):
         f = line.split()
-        if len(f) >= 3 and f[0] == kernel:
-            return float(f[1]) + float(f[2])
-    return None
+        if line.startswith("# kernel_sources_sha256:"):
+            taken_at = f[-1]
+        elif line.startswith("# commit:"):
+            commit = f[-1]
+        elif len(f) >= 3 and f[0] == kernel:
+            value = float(f[1]) + float(f[2])
+    info["commit"] = commit
+    info["kernel_sources_sha256_at_profile"] = taken_at
+    now = kernel_sources_sha256()
+    if taken_at != now:
+        info["note"] = f"stale: kernel sources now hash to {now}; figure withheld"
+        return None, info
+    return value, info
 
 
-def cpu_baseline(cfg, inp, sample_tokens):
-    """The fp64 oracle, as it stands, on the first `sample_tokens` tokens with the full weights."""
+# ------------------------------------------------------------------------------------------------
+# resident modules
+
+class ResidentModule:
+    """One module with its inputs and outputs in HBM and the calls of one phase bound to them."""
+
+    def __init__(self, cfg, tensors, mode, shared, D, torch, fused_forward=False):
+        self.cfg, self.mode, self.D = cfg, mode, D
+        dev, T, do, di, r = shared["dev"], cfg.tokens, cfg.d_out, cfg.d_in, cfg.r
+        td = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+        self.desc = D.make_desc(do, di, r, T, D.DORA_BF16 if cfg.dtype == "bf16" else D.DORA_F32, float(cfg.s), 0.0)
+        for k, v in tensors.items():
+            setattr(self, k, v)
+
+        def buf(name, shape, dtype):  # activation-sized outputs are shared between modules of one shape
+            key = (name, tuple(shape), dtype)
+            if key not in shared:
+                shared[key] = torch.empty(shape, dtype=dtype, device=dev)
+            return shared[key]
+
+        self.y = buf("y", (T, do), td)
+        self.c = torch.empty(do, dtype=torch.float32, device=dev)
+        self.h = self.inner = None
+        if mode == "fwd_bwd_saved":
+            self.h = torch.empty((T, r), dtype=td, device=dev)
+            self.inner = torch.empty((T, do), dtype=td, device=dev)
+        if mode != "fwd":
+            self.dx = buf("dx", (T, di), td)
+            self.dA = torch.empty((r, di), dtype=torch.float32, device=dev)
+            self.dB = torch.empty((do, r), dtype=torch.float32, device=dev)
+            self.dm = torch.empty(do, dtype=torch.float32, device=dev)
+        self.fwd_fn = D.dora_forward_fused if fused_forward else D.dora_forward
+        phases = [D.PHASE_FORWARD] + ([] if mode == "fwd" else
+                                      [D.PHASE_BACKWARD if mode == "fwd_bwd_saved" else D.PHASE_BACKWARD_RECOMPUTE])
+        self.ws_bytes = max(D.dora_workspace_bytes(self.desc, p) for p in phases)
+        self.ws = None  # set by the workload: one workspace shared by all modules
+
+    def forward(self, fwd_fn=None):
+        (fwd_fn or self.fwd_fn)(self.desc, self.x, self.W, self.A, self.B, self.m, None, None, self.y, self.h, self.inner,
+                                self.c if self.mode == "fwd_bwd_saved" else None, self.ws)
+
+    def backward(self):
+        if self.mode == "fwd_bwd_saved":
+            self.D.dora_backward(self.desc, self.dy, self.x, self.W, self.A, self.B, self.m, self.c, self.h, self.inner,
+                                 self.dx, self.dA, self.dB, self.dm, self.ws)
+        elif self.mode == "fwd_bwd_recompute":
+            self.D.dora_backward(self.desc, self.dy, self.x, self.W, self.A, self.B, self.m, None, None, None,
+                                 self.dx, self.dA, self.dB, self.dm, self.ws)
+
+
+def device_tensors(cfg, torch, dev, gen, with_dy):
+    """Synthetic inputs of one module drawn on the device (the sweep holds 224 modules; drawing 20 GB on the
+    host would take minutes).  Same recipe as inputs.make_inputs: W, A ~ N(0, var 1/d_in); B ~ N(0, std
+    sigma_B); x, dy ~ N(0, 1), each rounded once to the storage dtype; m = ||W||_row (1 + N(0, std sigma_m))."""
+    td = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+
+    def rn(shape, std):
+        return (torch.randn(shape, device=dev, generator=gen, dtype=torch.float32) * std).to(td)
+
+    inv = cfg.d_in ** -0.5
+    t = {"W": rn((cfg.d_out, cfg.d_in), inv), "A": rn((cfg.r, cfg.d_in), inv), "B": rn((cfg.d_out, cfg.r), cfg.sigma_B),
+         "x": rn((cfg.tokens, cfg.d_in), 1.0)}
+    row_norm = torch.linalg.vector_norm(t["W"].to(torch.float32), dim=1)
+    t["m"] = row_norm * (1.0 + cfg.sigma_m * torch.randn(cfg.d_out, device=dev, generator=gen, dtype=torch.float32))
+    if with_dy:
+        t["dy"] = rn((cfg.tokens, cfg.d_out), 1.0)
+    return t
+
+
+def host_tensors(cfg, G, I):
+    inp = I.make_inputs(cfg)
+    return {k: G.to_dev(inp[k]) for k in ("W", "A", "B", "m", "x", "dy")}, inp
+
+
+class Workload:
+    def __init__(self, name, modules, tokens, phase_text, torch, dev):
+        self.name, self.modules, self.tokens, self.phase_text = name, modules, tokens, phase_text
+        ws_bytes = max(m.ws_bytes for m in modules)
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        for m in modules:
+            m.ws = ws
+        self.ws_bytes = ws_bytes
+
+    def step(self):
+        for m in self.modules:
+            m.forward()
+        for m in reversed(self.modules):
+            m.backward()
+
+
+# ------------------------------------------------------------------------------------------------
+# timing
+
+def pct(sorted_vals, q):
+    if not sorted_vals:
+        return None
+    i = min(len(sorted_vals) - 1, max(0, int(round(q * (len(sorted_vals) - 1)))))
+    return sorted_vals[i]
+
+
+def time_steps(torch, fn, steps):
+    """Exactly `steps` calls of fn between two synchronisations: host-clock mean, and each call's own duration
+    from a pair of events on the launch stream."""
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for e0, e1 in evs:
+        e0.record()
+        fn()
+        e1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    per = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    return (t1 - t0) * 1e3 / steps, {"median": pct(per, 0.5), "p10": pct(per, 0.1), "p90": pct(per, 0.9),
+                                     "mean": sum(per) / len(per), "min": per[0], "max": per[-1], "n": len(per)}
+
+
+def kernel_table(D, torch, wl, reps, dominant_live):
+    """Every launch bracketed by HIP events, module by module, so that each kernel's time can be priced with the
+    algorithmic work of the module it ran for.  Returns the per-kernel list and the summed contraction rate."""
+    names = [D.dora_trace_name(k) for k in range(N_KERNEL_IDS)]
+    tot = {n: {"ms": 0.0, "launches": 0, "flops": 0.0, "bytes": 0.0} for n in names}
+
+    def traced(fn, work):
+        D.dora_trace_reset()
+        D.dora_trace_select(~0)
+        D.dora_trace_enable(True)
+        fn()
+        torch.cuda.synchronize()
+        D.dora_trace_enable(False)
+        D.dora_trace_collect()
+        got = {n: D.dora_trace_get(k) for k, n in enumerate(names)}
+        w = dict(work)
+        # launches that carry two contractions at once are priced with the work of both
+        if got["gemm_dA"][1] > 0 and got["gemm_dB"][1] == 0 and "gemm_dA" in w:
+            w["gemm_dA"] = (w["gemm_dA"][0] + w["gemm_dB"][0], w["gemm_dA"][1] + w["gemm_dB"][1])
+        for n, (ms, cnt) in got.items():
+            if cnt and n in w:
+                tot[n]["ms"] += ms
+                tot[n]["launches"] += cnt
+                tot[n]["flops"] += w[n][0] * cnt
+                tot[n]["bytes"] += w[n][1] * cnt
+
+    for _ in range(reps):
+        for m in wl.modules:
+            traced(m.forward, kernel_work(m.cfg, inner_saved=(m.mode == "fwd_bwd_saved")))
+        for m in reversed(wl.modules):
+            if m.mode != "fwd":
+                traced(m.backward, kernel_work(m.cfg, inner_saved=False))
+    fp32 = wl.modules[0].cfg.dtype != "bf16"
+    kernels = []
+    for n in names:
+        t = tot[n]
+        if t["launches"] == 0:
+            continue
+        live = dominant_live.get(n)
+        ms, cnt = (live if live and live[1] > 0 else (t["ms"], t["launches"]))
+        secs = ms * 1e-3 * (t["launches"] / cnt)          # total time of this kernel's launches in `reps` steps
+        hbm = n in HBM_BOUND
+        if hbm:
+            bound, ach, peak, unit = "hbm", t["bytes"] / secs / 1e9, PEAK_HBM_GBS, "GB/s"
+        elif fp32:
+            bound, ach, peak, unit = "alu", t["flops"] / secs / 1e12, PEAK_FP32_TFLOPS, "TFLOP/s"
+        else:
+            bound, ach, peak, unit = "mfma", t["flops"] / secs / 1e12, PEAK_BF16_TFLOPS, "TFLOP/s"
+        kernels.append({"kernel": n, "launches_per_step": t["launches"] / reps, "avg_us": secs / t["launches"] * 1e6,
+                        "us_per_step": secs / reps * 1e6, "bound": bound, "achieved": ach, "peak": peak, "unit": unit,
+                        "frac": ach / peak, "gbytes_per_s_algorithmic": t["bytes"] / secs / 1e9,
+                        "timed": "inside the timed steps" if live and live[1] > 0 else "separate pass, every launch bracketed"})
+    contr = [k for k in kernels if k["bound"] in ("mfma", "alu") and tot[k["kernel"]]["flops"] > 0]
+    flops = sum(tot[k["kernel"]]["flops"] for k in contr) / reps
+    secs = sum(k["us_per_step"] for k in contr) * 1e-6
+    return kernels, (flops / secs / 1e12 if secs > 0 else None)
+
+
+# ------------------------------------------------------------------------------------------------
+# CPU oracle leg
+
+def oracle_cores():
+    try:
+        from threadpoolctl import threadpool_info
+        return int(max([p.get("num_threads", 1) for p in threadpool_info()] or [1]))
+    except Exception:  # pragma: no cover
+        return os.cpu_count() or 1
+
+
+def cpu_baseline(samples, backward, note):
+    """The fp64 oracle, as it stands, on `samples` = [(cfg, stored host arrays, sample tokens)], repeated until
+    about ten seconds of CPU work are on the clock (at most 8 passes)."""
     import numpy as np
     from oracle import dora_oracle as O
     from paper_2603_22276_amd import inputs as I
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    except Exception:  # pragma: no cover
-        cores = os.cpu_count() or 1
-    n = min(sample_tokens, cfg.tokens)
-    W, A, B = I.to_f64(inp["W"]), I.to_f64(inp["A"]), I.to_f64(inp["B"])
-    x, dy = I.to_f64(inp["x"][:n]), I.to_f64(inp["dy"][:n])
-    m, s = inp["m"].astype(np.float64), float(inp["s"])
-    # the same sample again and again until about ten seconds of CPU work are on the clock (at most 8 passes)
+    cores = oracle_cores()
+    prepared = []
+    for cfg, inp, n in samples:
+        n = min(n, cfg.tokens)
+        prepared.append((cfg, n, I.to_f64(inp["W"]), I.to_f64(inp["A"]), I.to_f64(inp["B"]), I.to_f64(inp["x"][:n]),
+                         I.to_f64(inp["dy"][:n]) if backward else None, np.asarray(inp["m"], dtype=np.float64),
+                         float(inp["s"])))
     reps, dt = 0, 0.0
     while reps < 8 and dt < 10.0:
         t0 = time.perf_counter()
-        f = O.forward(x, W, A, B, m, s, cfg.eps)
-        O.backward(dy, x, W, A, B, m, s, cfg.eps, c=f["c"])
+        for cfg, n, W, A, B, x, dy, m, s in prepared:
+            f = O.forward(x, W, A, B, m, s, cfg.eps)
+            if backward:
+                O.backward(dy, x, W, A, B, m, s, cfg.eps, c=f["c"])
+            del f
         dt += time.perf_counter() - t0
         reps += 1
-        del f
-    return {"value": n * reps / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"fp64 numpy oracle, dense W+sBA norm + forward + backward, full weights, first {n} of "
-                      f"{cfg.tokens} tokens, {reps} passes, {dt:.1f} s"}
+    tokens = min(p[1] for p in prepared)   # every module of the sample sees the same number of tokens
+    return {"value": tokens * reps / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"fp64 numpy oracle (dense W+sBA norm, forward{', backward' if backward else ''}), full weights, "
+                      f"{note}, first {tokens} tokens, {reps} passes, {dt:.1f} s"}
 
+
+def to_host_inputs(mod, torch):
+    """Stored host arrays (the form the oracle leg widens) of a module whose inputs were drawn on the device."""
+    import numpy as np
+    out = {}
+    for k in ("W", "A", "B", "x", "dy"):
+        t = getattr(mod, k)
+        out[k] = t.view(torch.int16).cpu().numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.cpu().numpy()
+    out["m"] = mod.m.cpu().numpy()
+    out["s"] = mod.cfg.s
+    return out
+
+
+# ------------------------------------------------------------------------------------------------
+# the rank sweep of the norm in isolation (Sec. 5.6 / Table 5 on this machine)
 
 NORM_SWEEP_SHAPES = ((4096, 4096), (8192, 8192), (4096, 11008), (8192, 28672))   # shapes of Table 5
 NORM_SWEEP_RANKS = (16, 64, 128, 256, 384, 512, 768)
 
 
 def norm_sweep(reps: int):
-    """Rank sweep of the factored norm in isolation (the experiment of Sec. 5.6 / Table 5 on this machine).
-
-    For every shape and rank: dora_norm, dora_norm_cached (base term read from a [d_out] cache), the library's
+    """For every shape and rank: dora_norm, dora_norm_cached (base term read from a [d_out] cache), the library's
     scratch against one dense [d_out, d_in] temporary, and, for context only, the dense route in plain PyTorch
     ops on the same GPU (W + s * (B @ A), then a row norm: the computation the factored form replaces).
-    Weights are seeded synthetic bf16 with the stated distributions.  Prints one JSON line.
-    """
+    Weights are seeded synthetic bf16 with the stated distributions.  Prints one JSON line."""
     import torch
     from paper_2603_22276_amd import binding as D
     dev = "cuda:0"
@@ -156,17 +396,168 @@ def norm_sweep(reps: int):
                       "data": "synthetic", "reps": reps, "rows": rows}))
 
 
+# ------------------------------------------------------------------------------------------------
+
+def build_workload(name, args, torch, D, G, I, rank=None):
+    """-> (Workload, [(cfg, host inputs, sample tokens)] for the oracle leg, oracle note)"""
+    dev = G.DEV
+    shared = {"dev": dev}
+    if name in ("C1", "C2", "C3"):
+        cfg = {"C1": I.C1, "C2": I.C2, "C3": I.C3}[name]
+        mode = "fwd_bwd_saved" if name == "C3" else "fwd"
+        tensors, inp = host_tensors(cfg, G, I)
+        mod = ResidentModule(cfg, tensors, mode, shared, D, torch, fused_forward=args.fused_forward)
+        phase = ("forward (saves h, inner, w_norm) + backward (dx, dA, dB, dm)" if name == "C3"
+                 else "forward (factored norm, contractions, compose)")
+        wl = Workload(cfg.name, [mod], cfg.tokens, phase, torch, dev)
+        return wl, [(cfg, inp, args.cpu_sample_tokens or cfg.tokens)], "whole batch"
+    if name == "C4":
+        mods, samples = [], []
+        for cfg in (I.C4_UP, I.C4_DOWN):
+            tensors, inp = host_tensors(cfg, G, I)
+            mods.append(ResidentModule(cfg, tensors, "fwd_bwd_recompute", shared, D, torch))
+            samples.append((cfg, inp, args.cpu_sample_tokens or 1024))
+        wl = Workload("C4_bf16_mlp_pair_27648x5120_r384", mods, I.C4_UP.tokens,
+                      "forward of up and down keeping nothing, then backward of both with norm, h and inner recomputed",
+                      torch, dev)
+        return wl, samples, "up and down module"
+    if name == "C5":
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(I.BASE_SEED + 5000 + rank)
+        mods = []
+        for layer in range(args.c5_layers):
+            for mi in range(len(I.C5_MODULE_SHAPES)):
+                cfg = I.c5_module(mi, rank, layer=layer)
+                mods.append(ResidentModule(cfg, device_tensors(cfg, torch, dev, gen, True), "fwd_bwd_recompute", shared,
+                                           D, torch))
+        wl = Workload(f"C5_bf16_decoder_sweep_{args.c5_layers}x7_r{rank}", mods, mods[0].cfg.tokens,
+                      f"forward over {len(mods)} resident modules in order, then recompute + backward in reverse order",
+                      torch, dev)
+        samples = [(m.cfg, to_host_inputs(m, torch), args.cpu_sample_tokens or m.cfg.tokens) for m in mods[:7]]
+        return wl, samples, "the seven modules of layer 0 (the other layers repeat these shapes)"
+    raise ValueError(name)
+
+
+def measure(wl, args, torch, D, extras):
+    for _ in range(args.warmup):
+        wl.step()
+    torch.cuda.synchronize()
+    torch.cuda.reset_peak_memory_stats()
+    # timed region: exactly `steps` steps.  The library brackets the launches of the candidates for the dominant
+    # kernel (the two big contractions and the fused one) with HIP events on the launch stream; every other kernel
+    # is timed the same way in a second pass, so that the throughput figure does not carry ~30 event records per step.
+    D.dora_trace_reset()
+    D.dora_trace_select((1 << K_BASE) | (1 << K_DX) | (1 << K_FUSED))
+    D.dora_trace_enable(True)
+    ms_per_step, per_step = time_steps(torch, wl.step, args.steps)
+    D.dora_trace_enable(False)
+    D.dora_trace_collect()
+    live = {D.dora_trace_name(k): D.dora_trace_get(k) for k in (K_BASE, K_DX, K_FUSED)}
+    peak_mem = int(torch.cuda.max_memory_allocated())
+    if len(wl.modules) > 1:
+        live = {}   # several shapes share a kernel id: the per-module pass below prices each launch with its own work
+    reps = args.steps if len(wl.modules) == 1 else 1
+    kernels, contr_rate = kernel_table(D, torch, wl, reps, live)
+    dom = max(kernels, key=lambda k: k["us_per_step"])
+    traffic, tinfo = hbm_traffic(wl.name, dom["kernel"])
+    roofline = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
+                "unit": dom["unit"], "frac": dom["frac"], "traffic": traffic, "traffic_info": tinfo}
+    ms_untraced, _ = time_steps(torch, wl.step, args.steps)
+    out = {
+        "value": wl.tokens / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "step_ms_hip_events": per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "roofline": roofline,
+        "mfma_frac_all_contractions": (contr_rate / (PEAK_BF16_TFLOPS if dom["bound"] != "alu" else PEAK_FP32_TFLOPS)
+                                       if contr_rate else None),
+        "hbm_frac_compose_fwd": next((k["frac"] for k in kernels if k["kernel"] == "compose_fwd"), None),
+        "hbm_frac_compose_bwd": next((k["frac"] for k in kernels if k["kernel"] == "compose_bwd"), None),
+        "ms_per_step_without_event_pairs": ms_untraced,
+        "peak_device_memory_bytes": peak_mem,
+        "workspace_bytes_shared": wl.ws_bytes,
+        "kernels": kernels,
+    }
+    out.update(extras(wl, ms_untraced) if extras else {})
+    return out
+
+
+def c3_extras(args, torch, D, G):
+    """Figures reported beside `value` for the single bf16 modules: the step as a HIP graph, the other forward
+    path, and what this card sustains on a plain copy and a register-resident MFMA loop."""
+    def extras(wl, ms_untraced):
+        mod = wl.modules[0]
+        desc = mod.desc
+        out = {}
+        ms_graph = None
+        try:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                wl.step()
+            for _ in range(2):
+                graph.replay()
+            ms_graph, _ = time_steps(torch, graph.replay, args.steps)
+            del graph
+        except Exception as exc:  # pragma: no cover - informational figure only
+            print(f"bench.py: graph replay not measured ({exc})", file=sys.stderr)
+        out["ms_per_step_graph_replay"] = ms_graph
+        other = D.dora_forward if args.fused_forward else D.dora_forward_fused
+
+        def other_step():
+            mod.forward(other)
+            mod.backward()
+        for _ in range(2):
+            other_step()
+        ms_other, _ = time_steps(torch, other_step, args.steps)
+        out["other_forward_path"] = {
+            "forward_path": "base, lora, compose pass" if args.fused_forward else "fused epilogue",
+            "ms_per_step_without_event_pairs": ms_other, "tokens_per_s": wl.tokens / (ms_other * 1e-3)}
+        probe_bytes = 512 * 2 ** 20
+        src = torch.empty(probe_bytes, dtype=torch.uint8, device=G.DEV).fill_(1)
+        dst = torch.empty_like(src)
+        sink = torch.zeros(512, dtype=torch.float32, device=G.DEV)
+        probe_iters, probe_wgs = 512, 1024
+        for _ in range(2):
+            D.dora_probe_copy(src, dst, probe_bytes)
+            D.dora_probe_mfma(sink, probe_iters, probe_wgs)
+        torch.cuda.synchronize()
+        D.dora_trace_reset()
+        D.dora_trace_select(~0)
+        D.dora_trace_enable(True)
+        for _ in range(5):
+            D.dora_probe_copy(src, dst, probe_bytes)
+            D.dora_probe_mfma(sink, probe_iters, probe_wgs)
+        torch.cuda.synchronize()
+        D.dora_trace_enable(False)
+        D.dora_trace_collect()
+        copy_ms, copy_n = D.dora_trace_get(16)
+        mfma_ms, mfma_n = D.dora_trace_get(17)
+        out["sustained_on_this_card"] = {
+            "copy_GBps": 2.0 * probe_bytes / (copy_ms * 1e-3 / copy_n) / 1e9,
+            "mfma_bf16_TFLOPs": probe_wgs * 8 * probe_iters * 8 * 32768.0 / (mfma_ms * 1e-3 / mfma_n) / 1e12,
+            "note": "plain 16-byte-per-lane copy of 512 MiB (read + write counted) and a register-resident "
+                    "v_mfma_f32_32x32x16_bf16 loop, measured in this run"}
+        out["workspace_bytes"] = {"norm": D.dora_workspace_bytes(desc, D.PHASE_NORM),
+                                  "forward": D.dora_workspace_bytes(desc, D.PHASE_FORWARD),
+                                  "backward": D.dora_workspace_bytes(desc, D.PHASE_BACKWARD),
+                                  "dense_BA_temporary_avoided": mod.cfg.d_out * mod.cfg.d_in * 2}
+        return out
+    return extras
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="C3", choices=["C2", "C3"])
+    ap.add_argument("--config", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--c5-ranks", default="64,384,768", help="ranks of the decoder-layer sweep (comma separated)")
+    ap.add_argument("--c5-layers", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fused-forward", action="store_true",
                     help="forward through dora_forward_fused (compose folded into the GEMM epilogue) instead of the\n"
-                         "base / lora / compose sequence")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
+                         "base / lora / compose sequence (C2, C3)")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=0,
+                    help="tokens of the oracle's sample (default: the whole batch; 1024 per module for C4)")
     ap.add_argument("--norm-sweep", action="store_true",
                     help="instead of the step benchmark: time dora_norm alone over ranks and the weight shapes of Table 5")
     args = ap.parse_args()
@@ -180,190 +571,50 @@ def main():
 
     import torch
     from paper_2603_22276_amd import binding as D
-    from paper_2603_22276_amd import inputs as I
     from paper_2603_22276_amd import device as G
+    from paper_2603_22276_amd import inputs as I
 
-    cfg = {"C2": I.C2, "C3": I.C3}[args.config]
-    inp = I.make_inputs(cfg)
-    mod = G.Module(cfg, inp)
-    desc = mod.desc
-    T, do, di, r = cfg.tokens, cfg.d_out, cfg.d_in, cfg.r
-    bf = torch.bfloat16
-    y = torch.empty((T, do), dtype=bf, device=G.DEV)
-    h = torch.empty((T, r), dtype=bf, device=G.DEV)
-    inner = torch.empty((T, do), dtype=bf, device=G.DEV)
-    c = torch.empty(do, dtype=torch.float32, device=G.DEV)
-    dx = torch.empty((T, di), dtype=bf, device=G.DEV)
-    dA = torch.empty((r, di), dtype=torch.float32, device=G.DEV)
-    dB = torch.empty((do, r), dtype=torch.float32, device=G.DEV)
-    dm = torch.empty(do, dtype=torch.float32, device=G.DEV)
-    ws_f = G.workspace(desc, D.PHASE_FORWARD)
-    ws_b = G.workspace(desc, D.PHASE_BACKWARD)
+    if args.config != "C5":
+        wl, samples, note = build_workload(args.config, args, torch, D, G, I)
+        cfg = wl.modules[0].cfg
+        phase = {"C1": "fwd", "C2": "fwd", "C3": "fwd+bwd", "C4": "fwd+recompute+bwd"}[args.config]
+        out = {"metric": METRIC_FMT.format(phase=phase, d_in=cfg.d_in if args.config != "C4" else "5120/27648", r=cfg.r,
+                                           dtype="bf16" if cfg.dtype == "bf16" else "fp32")}
+        out.update(measure(wl, args, torch, D, c3_extras(args, torch, D, G) if args.config in ("C2", "C3") else None))
+        out.update({"dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+                    "config": {"workload": wl.name, "tokens": wl.tokens, "phase": wl.phase_text,
+                               "modules": [{"d_out": m.cfg.d_out, "d_in": m.cfg.d_in, "r": m.cfg.r} for m in wl.modules],
+                               "forward_path": "fused epilogue" if args.fused_forward else "base, lora, compose pass"}})
+        if len(wl.modules) == 1:
+            out["config"].update({"d_out": cfg.d_out, "d_in": cfg.d_in, "r": cfg.r})
+        out["cpu_baseline"] = None if args.no_cpu_baseline else cpu_baseline(samples, args.config in ("C3", "C4"), note)
+        print(json.dumps(out))
+        return
 
-    fwd = D.dora_forward_fused if args.fused_forward else D.dora_forward
-
-    def step():
-        fwd(desc, mod.x, mod.W, mod.A, mod.B, mod.m, None, None, y, h, inner, c, ws_f)
-        D.dora_backward(desc, mod.dy, mod.x, mod.W, mod.A, mod.B, mod.m, c, h, inner, dx, dA, dB, dm, ws_b)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-
-    # timed region: exactly `steps` steps.  The library brackets the launches of the candidates for the
-    # dominant kernel (the two big contractions and the fused one) with HIP events on the launch stream;
-    # every other kernel is timed the same way in a second pass below, so that the throughput figure
-    # does not carry ~30 event records per step.
-    K_BASE, K_DX, K_FUSED = 6, 13, 18
-    D.dora_trace_reset()
-    D.dora_trace_select((1 << K_BASE) | (1 << K_DX) | (1 << K_FUSED))
-    D.dora_trace_enable(True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    D.dora_trace_enable(False)
-    D.dora_trace_collect()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    dominant = {k: D.dora_trace_get(k) for k in (K_BASE, K_DX, K_FUSED)}
-
-    # second pass: every kernel bracketed (durations for the per-kernel table)
-    D.dora_trace_reset()
-    D.dora_trace_select(~0)
-    D.dora_trace_enable(True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms_all_events = (time.perf_counter() - t0) * 1e3 / args.steps
-    D.dora_trace_enable(False)
-    D.dora_trace_collect()
-
-    # the same number of steps without the event pairs, to show what they cost
-    def timed(fn):
-        torch.cuda.synchronize()
-        a = time.perf_counter()
-        for _ in range(args.steps):
-            fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - a) * 1e3 / args.steps
-
-    ms_untraced = timed(step)
-
-    # the same step captured once in a HIP graph and replayed: what is left of the gaps between the sixteen launches
-    ms_graph = None
-    try:
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            step()
-        for _ in range(2):
-            graph.replay()
-        ms_graph = timed(graph.replay)
-        del graph
-    except Exception as exc:  # pragma: no cover - informational figure only
-        print(f"bench.py: graph replay not measured ({exc})", file=sys.stderr)
-
-    # the other forward path (compose folded into the GEMM epilogue when the default is timed, and the
-    # other way round), same backward, no event pairs: reported beside `value`, not instead of it
-    other_fwd = D.dora_forward if args.fused_forward else D.dora_forward_fused
-
-    def other_step():
-        other_fwd(desc, mod.x, mod.W, mod.A, mod.B, mod.m, None, None, y, h, inner, c, ws_f)
-        D.dora_backward(desc, mod.dy, mod.x, mod.W, mod.A, mod.B, mod.m, c, h, inner, dx, dA, dB, dm, ws_b)
-
-    for _ in range(2):
-        other_step()
-    ms_other = timed(other_step)
-
-    # what this card sustains with no other work in the way: a plain streaming copy and a
-    # register-resident MFMA loop, timed the same way (library events on the launch stream)
-    probe_bytes = 512 * 2 ** 20
-    src = torch.empty(probe_bytes, dtype=torch.uint8, device=G.DEV).fill_(1)
-    dst = torch.empty_like(src)
-    sink = torch.zeros(512, dtype=torch.float32, device=G.DEV)
-    probe_iters, probe_wgs = 512, 1024
-    for _ in range(2):
-        D.dora_probe_copy(src, dst, probe_bytes)
-        D.dora_probe_mfma(sink, probe_iters, probe_wgs)
-    torch.cuda.synchronize()
-    D.dora_trace_enable(True)
-    for _ in range(5):
-        D.dora_probe_copy(src, dst, probe_bytes)
-        D.dora_probe_mfma(sink, probe_iters, probe_wgs)
-    torch.cuda.synchronize()
-    D.dora_trace_enable(False)
-    D.dora_trace_collect()
-    copy_ms, copy_n = D.dora_trace_get(16)
-    mfma_ms, mfma_n = D.dora_trace_get(17)
-    sustained = {
-        "copy_GBps": 2.0 * probe_bytes / (copy_ms * 1e-3 / copy_n) / 1e9,
-        "mfma_bf16_TFLOPs": probe_wgs * 8 * probe_iters * 8 * 32768.0 / (mfma_ms * 1e-3 / mfma_n) / 1e12,
-        "note": "plain 16-byte-per-lane copy of 512 MiB (read + write counted) and a register-resident "
-                "v_mfma_f32_32x32x16_bf16 loop, measured in this run",
-    }
-    del src, dst
-
-    work = kernel_work(cfg)
-    # launches that carry two contractions at once are priced with the work of both
-    for host, guest in (("gemm_base_xWt", "gemm_h_xAt"), ("gemm_dA", "gemm_dB")):
-        names = [D.dora_trace_name(k) for k in range(16)]
-        if D.dora_trace_get(names.index(guest))[1] == 0:
-            work[host] = (work[host][0] + work[guest][0], work[host][1] + work[guest][1])
-    kernels = []
-    for kid in list(range(16)) + [18]:
-        total_ms, n = D.dora_trace_get(kid)
-        if kid in dominant and dominant[kid][1] > 0:
-            total_ms, n = dominant[kid]  # the duration measured inside the timed region
-        if n == 0:
-            continue
-        name = D.dora_trace_name(kid)
-        avg_s = total_ms * 1e-3 / n
-        flops, nbytes = work[name]
-        hbm = name in HBM_BOUND
-        ach = (nbytes / avg_s / 1e9) if hbm else (flops / avg_s / 1e12)
-        peak = PEAK_HBM_GBS if hbm else PEAK_BF16_TFLOPS
-        kernels.append({"kernel": name, "launches_per_step": n / args.steps, "avg_us": avg_s * 1e6,
-                        "bound": "hbm" if hbm else "mfma", "achieved": ach, "peak": peak,
-                        "unit": "GB/s" if hbm else "TFLOP/s", "frac": ach / peak,
-                        "gbytes_per_s_algorithmic": nbytes / avg_s / 1e9})
-    dom = max(kernels, key=lambda k: k["avg_us"] * k["launches_per_step"])
-    roofline = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
-                "unit": dom["unit"], "frac": dom["frac"], "traffic": hbm_traffic(cfg.name, dom["kernel"])}
-    mfma = [k for k in kernels if k["bound"] == "mfma" and work[k["kernel"]][0] > 0]
-    mfma_flops = sum(work[k["kernel"]][0] * k["launches_per_step"] for k in mfma)
-    mfma_time = sum(k["avg_us"] * 1e-6 * k["launches_per_step"] for k in mfma)
-
-    out = {
-        "metric": "DoRA fwd+bwd tokens/s at d_in=8192 r=384 bf16; %MFMA and %HBM peak",
-        "value": T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": cfg.name, "d_out": do, "d_in": di, "r": r, "tokens": T,
-                   "phase": "forward (saves h, inner, w_norm) + backward (dx, dA, dB, dm)",
-                   "forward_path": "fused epilogue" if args.fused_forward else "base, lora, compose pass"},
-        "roofline": roofline,
-        "mfma_frac_all_contractions": mfma_flops / mfma_time / 1e12 / PEAK_BF16_TFLOPS,
-        "hbm_frac_compose_fwd": next((k["frac"] for k in kernels if k["kernel"] == "compose_fwd"), None),
-        "hbm_frac_compose_bwd": next(k["frac"] for k in kernels if k["kernel"] == "compose_bwd"),
-        "ms_per_step_without_event_pairs": ms_untraced,
-        "ms_per_step_with_every_kernel_bracketed": ms_all_events,
-        "ms_per_step_graph_replay": ms_graph,
-        "other_forward_path": {"forward_path": "base, lora, compose pass" if args.fused_forward else "fused epilogue",
-                               "ms_per_step_without_event_pairs": ms_other, "tokens_per_s": T / (ms_other * 1e-3)},
-        "sustained_on_this_card": sustained,
-        "workspace_bytes": {"norm": D.dora_workspace_bytes(desc, D.PHASE_NORM),
-                            "forward": D.dora_workspace_bytes(desc, D.PHASE_FORWARD),
-                            "backward": D.dora_workspace_bytes(desc, D.PHASE_BACKWARD),
-                            "dense_BA_temporary_avoided": do * di * 2},
-        "kernels": kernels,
-    }
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, inp, args.cpu_sample_tokens)
-    else:
-        out["cpu_baseline"] = None
+    # C5: one sweep per rank; `value` is the aggregate rate at r = 384 (the headline rank), the others beside it
+    ranks = [int(v) for v in args.c5_ranks.split(",")]
+    per_rank, cpu = {}, None
+    for rank in ranks:
+        wl, samples, note = build_workload("C5", args, torch, D, G, I, rank=rank)
+        res = measure(wl, args, torch, D, None)
+        res["config"] = {"workload": wl.name, "tokens": wl.tokens, "phase": wl.phase_text, "r": rank,
+                         "modules_resident": len(wl.modules)}
+        per_rank[rank] = res
+        if not args.no_cpu_baseline and (rank == 384 or (384 not in ranks and rank == ranks[-1])):
+            cpu = cpu_baseline(samples, True, note)
+            per_layer_s = min(s[2] for s in samples) / cpu["value"]
+            cpu["sample"] += (f"; one layer takes {per_layer_s:.1f} s, so the {args.c5_layers}-layer sweep is put at "
+                              f"{args.c5_layers * per_layer_s:.0f} s by extrapolation: `value` is tokens / that")
+            cpu["value"] = cpu["value"] / args.c5_layers
+        del wl, samples
+        torch.cuda.empty_cache()
+    head = per_rank.get(384) or per_rank[ranks[-1]]
+    out = {"metric": "DoRA fwd+recompute+bwd aggregate tokens/s over a 32-layer decoder sweep (7 adapted modules per layer) "
+                     "at r=384 bf16; %MFMA and %HBM peak"}
+    out.update({k: v for k, v in head.items() if k != "config"})
+    out.update({"dtype": "bf16", "data": "synthetic", "config": head["config"],
+                "ranks": {str(r): {k: v for k, v in res.items() if k != "kernels"} for r, res in per_rank.items()},
+                "cpu_baseline": cpu})
     print(json.dumps(out))
 
 
