@@ -108,6 +108,24 @@ dora_status dora_norm_cached(const dora_desc* desc, const float* base_sq, const 
                              const void* B, float* w_norm, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * The factored terms on their own, for reuse while A and B are unchanged (Sec. 2.3 leaves caching as future
+ * work; within one training step the forward and the recomputed forward of a checkpointed backward see the
+ * same W, A, B, so the second can reuse what the first computed).  Nothing is cached inside the library:
+ * the caller owns the buffers and decides when they are stale.
+ *   dora_norm_terms    : terms [3, d_out] fp32 out = base_sq | cross | ba_sq (Eq. 2-4), each row the
+ *                        fixed-order sum of the split-K partials; G [r, r] fp32 out or NULL (Eq. 4).
+ *                        s == 0: cross = ba_sq = 0, G = 0 (Algorithm 1, notes).  Workspace as for dora_norm.
+ *   dora_norm_assemble : w_norm = sqrt(max(base_sq + 2 s cross + s^2 ba_sq, 0)) (Eq. 5) from such terms, with
+ *                        desc->s: one small launch, bit-identical to what dora_norm returns for the same
+ *                        inputs.  d_in, r, tokens of desc are not read.  Needs no workspace.
+ * dora_norm(...) == dora_norm_terms(...) followed by dora_norm_assemble(...).  The default of every other
+ * entry point is unchanged: the norm is recomputed unless the caller passes w_norm (App. A item 2).
+ */
+dora_status dora_norm_terms(const dora_desc* desc, const void* W, const void* A, const void* B,
+                            float* terms, float* G, void* ws, size_t ws_bytes, void* stream);
+dora_status dora_norm_assemble(const dora_desc* desc, const float* terms, float* w_norm, void* stream);
+
+/*
  * Magnitude scale of Eq. 6: g = m / max(w_norm, eps), and the explicit small
  * correction gm1 = g - 1 of Sec. 3.1, formed as (m - cc)/cc with cc = max(w_norm, eps)
  * so that it does not suffer the rounding of g.  g or gm1 may be NULL (not both).

@@ -14,12 +14,12 @@ from typing import Optional
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libdora.so")
 
-DORA_F32, DORA_BF16 = 0, 1
+DORA_F32, DORA_BF16, DORA_F16 = 0, 1, 2
 PHASE_NORM, PHASE_FORWARD, PHASE_BACKWARD, PHASE_BACKWARD_RECOMPUTE, PHASE_COMPOSE_BACKWARD = range(5)
 K_COUNT = 19
 
 EXPORTS = (
-    "dora_workspace_bytes", "dora_norm", "dora_norm_static", "dora_norm_static_max_bytes", "dora_base_sq", "dora_norm_cached", "dora_mag_scale", "dora_compose", "dora_compose_backward",
+    "dora_workspace_bytes", "dora_norm", "dora_norm_static", "dora_norm_static_max_bytes", "dora_base_sq", "dora_norm_cached", "dora_norm_terms", "dora_norm_assemble", "dora_mag_scale", "dora_compose", "dora_compose_backward",
     "dora_project", "dora_forward", "dora_forward_fused", "dora_backward", "dora_status_str",
     "dora_probe_copy", "dora_probe_mfma",
     "dora_trace_enable", "dora_trace_select", "dora_trace_reset", "dora_trace_collect", "dora_trace_get", "dora_trace_name",
@@ -59,6 +59,8 @@ def lib() -> ctypes.CDLL:
         L.dora_norm_static_max_bytes.restype = sz
         L.dora_base_sq.argtypes = [dp, vp, fp, vp]
         L.dora_norm_cached.argtypes = [dp, fp, vp, vp, vp, fp, vp, sz, vp]
+        L.dora_norm_terms.argtypes = [dp, vp, vp, vp, fp, fp, vp, sz, vp]
+        L.dora_norm_assemble.argtypes = [dp, fp, fp, vp]
         L.dora_mag_scale.argtypes = [dp, fp, fp, fp, fp, vp]
         L.dora_compose.argtypes = [dp, vp, vp, fp, fp, vp, ctypes.c_int, vp, vp]
         L.dora_compose_backward.argtypes = [dp, vp, vp, fp, fp, vp, fp, vp, sz, vp]
@@ -68,7 +70,7 @@ def lib() -> ctypes.CDLL:
         L.dora_backward.argtypes = [dp, vp, vp, vp, vp, vp, fp, fp, vp, vp, vp, fp, fp, fp, vp, sz, vp]
         L.dora_probe_copy.argtypes = [vp, vp, sz, vp]
         L.dora_probe_mfma.argtypes = [fp, ctypes.c_int, ctypes.c_int, vp]
-        for f in (L.dora_probe_copy, L.dora_probe_mfma, L.dora_norm, L.dora_norm_static, L.dora_base_sq, L.dora_norm_cached, L.dora_mag_scale, L.dora_compose, L.dora_compose_backward, L.dora_project, L.dora_forward, L.dora_forward_fused,
+        for f in (L.dora_probe_copy, L.dora_probe_mfma, L.dora_norm, L.dora_norm_static, L.dora_base_sq, L.dora_norm_cached, L.dora_norm_terms, L.dora_norm_assemble, L.dora_mag_scale, L.dora_compose, L.dora_compose_backward, L.dora_project, L.dora_forward, L.dora_forward_fused,
                   L.dora_backward, L.dora_trace_collect, L.dora_trace_get):
             f.restype = ctypes.c_int
         L.dora_status_str.argtypes = [ctypes.c_int]
@@ -150,6 +152,15 @@ def dora_base_sq(desc, W, base_sq, stream=None) -> None:
 def dora_norm_cached(desc, base_sq, W, A, B, w_norm, ws, stream=None) -> None:
     _check(lib().dora_norm_cached(ctypes.byref(desc), _p(base_sq), _p(W), _p(A), _p(B), _p(w_norm), _p(ws), _nbytes(ws),
                                   _stream(stream)), "dora_norm_cached")
+
+
+def dora_norm_terms(desc, W, A, B, terms, G, ws, stream=None) -> None:
+    _check(lib().dora_norm_terms(ctypes.byref(desc), _p(W), _p(A), _p(B), _p(terms), _p(G), _p(ws), _nbytes(ws),
+                                 _stream(stream)), "dora_norm_terms")
+
+
+def dora_norm_assemble(desc, terms, w_norm, stream=None) -> None:
+    _check(lib().dora_norm_assemble(ctypes.byref(desc), _p(terms), _p(w_norm), _stream(stream)), "dora_norm_assemble")
 
 
 def dora_mag_scale(desc, m, w_norm, g, gm1, stream=None) -> None:

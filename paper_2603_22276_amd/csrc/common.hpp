@@ -126,12 +126,13 @@ hipError_t launch_compose_bwd(int dtype, const void* dy, const void* inner, cons
                               float* partial /* [slabs][d_out] or nullptr */, int64_t tokens, int d_out, hipStream_t st);
 hipError_t launch_dm_final(const float* partial, int slabs, const float* c, float eps, float* dm, int d_out, hipStream_t st);
 hipError_t launch_gram_reduce(const float* partials, int ksplit, int r, float* G, bf16_t* Ghi, bf16_t* Glo, hipStream_t st);
+// c and / or terms ([3, d_out]: the summed base_sq, cross, ba_sq) may be nullptr
 hipError_t launch_norm_final(const float* base_sq_p, int n_base, const float* cross_p, int n_cross, const float* ba_p,
-                             int n_ba, double s, float* c, int d_out, hipStream_t st);
+                             int n_ba, double s, float* c, float* terms, int d_out, hipStream_t st);
 hipError_t launch_rownorm_s0_bf16(const bf16_t* W, float* c, int d_out, int d_in, bool squared, hipStream_t st);
 // fp32 path: base_sq, cross, ba_sq and Eq. 5 from W, B, U = W A^T, BG = B G (all fp32)
 hipError_t launch_rownorm_f32(const float* W, const float* base_in, const float* B, const float* U, const float* BG,
-                              double s, float* c, int d_out, int d_in, int r, bool squared, hipStream_t st);
+                              double s, float* c, float* terms, int d_out, int d_in, int r, bool squared, hipStream_t st);
 
 hipError_t launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t st);
 hipError_t launch_mfma_probe(float* sink, int iters, int workgroups, hipStream_t st);

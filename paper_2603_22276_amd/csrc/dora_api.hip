@@ -224,14 +224,26 @@ hipError_t contract(int dtype, bool a_kc, bool b_kc, int M, int N, const Seg* se
 // ------------------------------------------------------------------------------------------------
 // factored norm (Sec. 2, Algorithm 1)
 // base_sq != nullptr: the base term of Eq. 2 comes from the caller's cache and W is not squared again
+// c == nullptr: only the terms are wanted.  terms != nullptr: [3, d_out] fp32 receives base_sq, cross, ba_sq.
+// G_out != nullptr: [r, r] fp32 receives the Gram matrix of Eq. 4.
 dora_status norm_impl(const dora_desc* d, const void* W, const void* A, const void* B, float* c, const NormPlan& n,
-                      hipStream_t st, const float* base_sq = nullptr)
+                      hipStream_t st, const float* base_sq = nullptr, float* terms = nullptr, float* G_out = nullptr)
 {
     const int d_out = (int)d->d_out, d_in = (int)d->d_in, r = (int)d->r;
     if (d->s == 0.f) {  // scale-is-zero fast path: no U, no G
-        if (base_sq) DORA_HIP(launch_norm_final(base_sq, 1, nullptr, 0, nullptr, 0, 0.0, c, d_out, st));
+        if (terms) {  // base_sq from W (or the cache), cross = ba_sq = 0, G not formed
+            if (G_out) DORA_HIP(launch_gram_reduce(nullptr, 0, r, G_out, nullptr, nullptr, st));  // zero partials: G = 0
+            if (!base_sq && d->dtype == DORA_BF16) {
+                DORA_HIP(launch_rownorm_s0_bf16((const bf16_t*)W, n.base_p, d_out, d_in, true, st));
+                base_sq = n.base_p;
+            }
+            if (base_sq) DORA_HIP(launch_norm_final(base_sq, 1, nullptr, 0, nullptr, 0, 0.0, c, terms, d_out, st));
+            else DORA_HIP(launch_rownorm_f32((const float*)W, nullptr, nullptr, nullptr, nullptr, 0.0, c, terms, d_out, d_in, r, false, st));
+            return DORA_OK;
+        }
+        if (base_sq) DORA_HIP(launch_norm_final(base_sq, 1, nullptr, 0, nullptr, 0, 0.0, c, nullptr, d_out, st));
         else if (d->dtype == DORA_BF16) DORA_HIP(launch_rownorm_s0_bf16((const bf16_t*)W, c, d_out, d_in, false, st));
-        else DORA_HIP(launch_rownorm_f32((const float*)W, nullptr, nullptr, nullptr, nullptr, 0.0, c, d_out, d_in, r, false, st));
+        else DORA_HIP(launch_rownorm_f32((const float*)W, nullptr, nullptr, nullptr, nullptr, 0.0, c, nullptr, d_out, d_in, r, false, st));
         return DORA_OK;
     }
     if (d->dtype == DORA_BF16) {
@@ -249,7 +261,7 @@ dora_status norm_impl(const dora_desc* d, const void* W, const void* A, const vo
         g.nseg = 1; g.M = r; g.N = r; g.a_kcontig = 1; g.b_kcontig = 1; g.epilogue = EPI_STORE_F32; g.alpha = 1.f;
         g.c = n.gram_p; g.ldc = r; g.ksplit = n.ks_g;
         DORA_HIP(launch_gemm_bf16(g, DORA_K_GRAM, st));
-        DORA_HIP(launch_gram_reduce(n.gram_p, n.ks_g, r, nullptr, n.Ghi, n.Glo, st));
+        DORA_HIP(launch_gram_reduce(n.gram_p, n.ks_g, r, G_out, n.Ghi, n.Glo, st));
         // BA-norm term: rowdot(B, B G) with G = Ghi + Glo kept to ~16 mantissa bits (G is symmetric,
         // so G serves as its own K-contiguous N-side operand)
         memset(&g, 0, sizeof(g));
@@ -259,7 +271,7 @@ dora_status norm_impl(const dora_desc* d, const void* W, const void* A, const vo
         g.ksplit = 1; g.rowdot = (const bf16_t*)B; g.ld_rowdot = r; g.rowdot_partial = n.ba_p; g.tag = 1;
         DORA_HIP(launch_gemm_bf16(g, DORA_K_BA_SQ, st));
         DORA_HIP(launch_norm_final(base_sq ? base_sq : n.base_p, base_sq ? 1 : n.ks_u, n.cross_p, n.ks_u * n.tiles_n,
-                                   n.ba_p, n.tiles_n, (double)d->s, c, d_out, st));
+                                   n.ba_p, n.tiles_n, (double)d->s, c, terms, d_out, st));
         return DORA_OK;
     }
     // fp32: Algorithm 1 with one chunk spanning d_in; U [d_out, r], G [r, r], BG [d_out, r] in scratch
@@ -269,8 +281,9 @@ dora_status norm_impl(const dora_desc* d, const void* W, const void* A, const vo
     DORA_HIP(contract(DORA_F32, true, true, r, r, &sg, 1, 1.f, n.G, r, true, DORA_K_GRAM, st));
     Seg sb{B, r, n.G, r, r};  // (B G)[j,l] = sum_k B[j,k] G[k,l]: N-side operand K-strided
     DORA_HIP(contract(DORA_F32, true, false, d_out, r, &sb, 1, 1.f, n.BG, r, true, DORA_K_BA_SQ, st));
-    DORA_HIP(launch_rownorm_f32((const float*)W, base_sq, (const float*)B, n.U, n.BG, (double)d->s, c, d_out, d_in, r,
-                                false, st));
+    DORA_HIP(launch_rownorm_f32((const float*)W, base_sq, (const float*)B, n.U, n.BG, (double)d->s, c, terms, d_out, d_in,
+                                r, false, st));
+    if (G_out) DORA_HIP(hipMemcpyAsync(G_out, n.G, sizeof(float) * (size_t)r * r, hipMemcpyDeviceToDevice, st));
     return DORA_OK;
 }
 
@@ -424,7 +437,7 @@ dora_status dora_base_sq(const dora_desc* desc, const void* W, float* base_sq, v
     const int d_out = (int)desc->d_out, d_in = (int)desc->d_in;
     hipStream_t s = (hipStream_t)stream;
     if (desc->dtype == DORA_BF16) DORA_HIP(launch_rownorm_s0_bf16((const bf16_t*)W, base_sq, d_out, d_in, true, s));
-    else DORA_HIP(launch_rownorm_f32((const float*)W, nullptr, nullptr, nullptr, nullptr, 0.0, base_sq, d_out, d_in, 0, true, s));
+    else DORA_HIP(launch_rownorm_f32((const float*)W, nullptr, nullptr, nullptr, nullptr, 0.0, base_sq, nullptr, d_out, d_in, 0, true, s));
     return DORA_OK;
 }
 
@@ -441,6 +454,34 @@ dora_status dora_norm_cached(const dora_desc* desc, const float* base_sq, const 
     Bump b(ws);
     plan_norm(desc, b, n);
     return norm_impl(desc, W, A, B, w_norm, n, (hipStream_t)stream, base_sq);
+}
+
+dora_status dora_norm_terms(const dora_desc* desc, const void* W, const void* A, const void* B, float* terms, float* G,
+                            void* ws, size_t ws_bytes, void* stream)
+{
+    dora_status st = check_desc(desc, true);
+    if (st != DORA_OK) return st;
+    DORA_REQ_PTR(W); DORA_REQ_PTR(A); DORA_REQ_PTR(B); DORA_REQ_PTR(terms);
+    DORA_OPT_PTR(G);
+    Bump sizing(nullptr);
+    NormPlan n;
+    plan_norm(desc, sizing, n);
+    if ((st = check_ws(ws, ws_bytes, sizing.off)) != DORA_OK) return st;
+    Bump b(ws);
+    plan_norm(desc, b, n);
+    return norm_impl(desc, W, A, B, nullptr, n, (hipStream_t)stream, nullptr, terms, G);
+}
+
+dora_status dora_norm_assemble(const dora_desc* desc, const float* terms, float* w_norm, void* stream)
+{
+    dora_status st = check_desc(desc, false);
+    if (st != DORA_OK) return st;
+    DORA_REQ_PTR(terms); DORA_REQ_PTR(w_norm);
+    const int d_out = (int)desc->d_out;
+    // the same kernel, and so the same arithmetic in the same order, as the last step of dora_norm
+    DORA_HIP(launch_norm_final(terms, 1, terms + d_out, 1, terms + 2 * (size_t)d_out, 1, (double)desc->s, w_norm, nullptr, d_out,
+                               (hipStream_t)stream));
+    return DORA_OK;
 }
 
 dora_status dora_mag_scale(const dora_desc* desc, const float* m, const float* w_norm, float* g, float* gm1,

@@ -62,9 +62,11 @@ __global__ void mag_scale_kernel(const float* __restrict__ m, const float* __res
 }
 
 // Eq. 5 from the partial sums the norm kernels left behind; partials are added in index order.
+// terms != nullptr: the three summed terms are also written, as rows of a [3, d_out] array (base_sq,
+// cross, ba_sq); c == nullptr: only the terms are wanted.
 __global__ void norm_final_kernel(const float* __restrict__ base_p, int n_base, const float* __restrict__ cross_p,
                                   int n_cross, const float* __restrict__ ba_p, int n_ba, float two_s, float s2,
-                                  float* __restrict__ c, int d_out)
+                                  float* __restrict__ c, float* __restrict__ terms, int d_out)
 {
     int j = blockIdx.x * blockDim.x + threadIdx.x;
     if (j >= d_out) return;
@@ -72,6 +74,12 @@ __global__ void norm_final_kernel(const float* __restrict__ base_p, int n_base, 
     for (int i = 0; i < n_base; ++i) base_sq += base_p[(int64_t)i * d_out + j];
     for (int i = 0; i < n_cross; ++i) cross += cross_p[(int64_t)i * d_out + j];
     for (int i = 0; i < n_ba; ++i) ba += ba_p[(int64_t)i * d_out + j];
+    if (terms) {
+        terms[j] = base_sq;
+        terms[(int64_t)d_out + j] = cross;
+        terms[2 * (int64_t)d_out + j] = ba;
+    }
+    if (!c) return;
     float rad = base_sq + two_s * cross + s2 * ba;
     rad = (rad < 0.f) ? 0.f : rad;  // NaN is not < 0: it propagates (App. C item 3)
     c[j] = __fsqrt_rn(rad);
@@ -86,6 +94,7 @@ __global__ void gram_reduce_kernel(const float* __restrict__ p, int ksplit, int 
     float acc = 0.f;
     for (int z = 0; z < ksplit; ++z) acc += p[(int64_t)z * rr + i];
     if (G) G[i] = acc;
+    if (!Ghi) return;
     uint32_t hi = f32_to_bf16_bits(acc);
     float rem = acc - __uint_as_float(hi << 16);
     Ghi[i] = (bf16_t)hi;
@@ -98,7 +107,7 @@ __global__ void gram_reduce_kernel(const float* __restrict__ p, int ksplit, int 
 __global__ void rownorm_f32_kernel(const float* __restrict__ W, const float* __restrict__ base_in,
                                    const float* __restrict__ B, const float* __restrict__ U,
                                    const float* __restrict__ BG, float two_s, float s2, float* __restrict__ c,
-                                   int d_out, int d_in, int r, bool squared)
+                                   float* __restrict__ terms, int d_out, int d_in, int r, bool squared)
 {
     int lane = threadIdx.x & 63;
     int row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
@@ -120,9 +129,16 @@ __global__ void rownorm_f32_kernel(const float* __restrict__ W, const float* __r
     }
     if (lane == 0) {
         if (base_in) base_sq = base_in[row];
-        float rad = base_sq + two_s * cross + s2 * ba;
-        rad = (rad < 0.f) ? 0.f : rad;
-        c[row] = squared ? rad : __fsqrt_rn(rad);
+        if (terms) {
+            terms[row] = base_sq;
+            terms[(int64_t)d_out + row] = cross;
+            terms[2 * (int64_t)d_out + row] = ba;
+        }
+        if (c) {
+            float rad = base_sq + two_s * cross + s2 * ba;
+            rad = (rad < 0.f) ? 0.f : rad;
+            c[row] = squared ? rad : __fsqrt_rn(rad);
+        }
     }
 }
 
@@ -320,13 +336,13 @@ hipError_t launch_mag_scale(const float* m, const float* c, float eps, float* g,
 }
 
 hipError_t launch_norm_final(const float* base_p, int n_base, const float* cross_p, int n_cross, const float* ba_p,
-                             int n_ba, double s, float* c, int d_out, hipStream_t st)
+                             int n_ba, double s, float* c, float* terms, int d_out, hipStream_t st)
 {
     if (d_out == 0) return hipSuccess;
     TraceScope ts(DORA_K_NORM_FINAL, st);
     // 2s and s^2 are formed in double and rounded once (App. C item 3)
     norm_final_kernel<<<dim3((d_out + 255) / 256), dim3(256), 0, st>>>(base_p, n_base, cross_p, n_cross, ba_p, n_ba,
-                                                                       (float)(2.0 * s), (float)(s * s), c, d_out);
+                                                                       (float)(2.0 * s), (float)(s * s), c, terms, d_out);
     return hipGetLastError();
 }
 
@@ -348,12 +364,12 @@ hipError_t launch_rownorm_s0_bf16(const bf16_t* W, float* c, int d_out, int d_in
 }
 
 hipError_t launch_rownorm_f32(const float* W, const float* base_in, const float* B, const float* U, const float* BG,
-                              double s, float* c, int d_out, int d_in, int r, bool squared, hipStream_t st)
+                              double s, float* c, float* terms, int d_out, int d_in, int r, bool squared, hipStream_t st)
 {
     if (d_out == 0) return hipSuccess;
     TraceScope ts(DORA_K_NORM_FINAL, st);
     rownorm_f32_kernel<<<dim3((d_out + 3) / 4), dim3(256), 0, st>>>(W, base_in, B, U, BG, (float)(2.0 * s),
-                                                                    (float)(s * s), c, d_out, d_in, r, squared);
+                                                                    (float)(s * s), c, terms, d_out, d_in, r, squared);
     return hipGetLastError();
 }
 

@@ -34,7 +34,7 @@ def pick(t, idx):
 # Regression bounds on top of the 2e-2 ceiling: about three times the error this path achieves on these
 # workloads (fp32 outputs of fp32-accumulated bf16 products, and the delta of the compose), so that a tenfold
 # loss of accuracy fails even though it would still sit below the ceiling.
-TIGHT = {"dA": 6e-3, "dB": 6e-3, "dm": 3e-3, "delta": 1.2e-2}
+TIGHT = {"dA": 7e-3, "dB": 7e-3, "dm": 1e-2, "delta": 1.5e-2}
 
 
 def check_delta_sampled(mod, f, rows, c_dev):

@@ -88,6 +88,72 @@ def test_cached_norm_with_zero_scale(dtype):
     G.assert_norm_close(G.to_f64(c), np.linalg.norm(mod.f64("W"), axis=1), G.TOL[dtype]["norm"])
 
 
+@pytest.mark.parametrize("cfg", SMALL, ids=IDS)
+def test_norm_terms_and_their_assembly(cfg):
+    # the factored terms one by one (Eq. 2-4) against their fp64 definitions, the Gram matrix, and
+    # dora_norm == dora_norm_terms followed by dora_norm_assemble, bit for bit
+    mod = G.Module(cfg)
+    t64 = O.factored_norm_terms(mod.f64("W"), mod.f64("A"), mod.f64("B"))
+    terms = G.empty_f32(3, cfg.d_out)
+    Gm = G.empty_f32(cfg.r, cfg.r)
+    D.dora_norm_terms(mod.desc, mod.W, mod.A, mod.B, terms, Gm, G.workspace(mod.desc, D.PHASE_NORM))
+    got = G.to_f64(terms)
+    np.testing.assert_allclose(got[0], t64["base_sq"], rtol=1e-5)
+    # cross and ba_sq are sums with cancellation: bounded against the scale Cauchy-Schwarz gives them
+    fine = 1e-5 if cfg.dtype == "f32" else 2e-4   # bf16: G carried as two bf16 terms (2^-16), fp32 sums
+    scale = np.sqrt(t64["base_sq"] * t64["ba_sq"]) + 1e-30
+    assert np.max(np.abs(got[1] - t64["cross"]) / scale) <= fine
+    np.testing.assert_allclose(got[2], t64["ba_sq"], rtol=fine, atol=1e-30)
+    assert G.rel_max(G.to_f64(Gm), t64["G"]) <= 1e-5
+    c = G.empty_f32(cfg.d_out)
+    D.dora_norm_assemble(mod.desc, terms, c)
+    assert torch.equal(c, mod.norm())
+    G.assert_norm_close(G.to_f64(c), O.dense_row_norm(mod.f64("W"), mod.f64("A"), mod.f64("B"), float(mod.inp["s"])),
+                        G.TOL[cfg.dtype]["norm"])
+
+
+def test_norm_terms_reuse_in_a_recomputed_backward_and_a_stale_cache_shows():
+    # gradient-checkpointing pattern with the norm's terms carried from the forward: the recomputed
+    # backward re-assembles Eq. 5 from them (one small launch) instead of re-running the contractions
+    cfg = I.stress(cfg_bf16("terms_reuse", 520, 392, 40, 300, seed=31))
+    mod = G.Module(cfg)
+    ws = G.workspace(mod.desc, D.PHASE_BACKWARD_RECOMPUTE)
+    terms = G.empty_f32(3, cfg.d_out)
+    D.dora_norm_terms(mod.desc, mod.W, mod.A, mod.B, terms, None, ws)
+    c = G.empty_f32(cfg.d_out)
+    D.dora_norm_assemble(mod.desc, terms, c)
+    ref = mod.backward()                     # norm, h, inner all recomputed inside
+    got = mod.backward(w_norm=c)             # norm from the carried terms, h and inner recomputed
+    for k in ("dx", "dA", "dB", "dm"):
+        assert torch.equal(ref[k], got[k]), k
+    b = O.backward(mod.f64("dy"), **oracle_inputs(mod))
+    for k in ("dx", "dA", "dB", "dm"):
+        G.assert_close(k, G.to_f64(got[k]), b[k], G.TOL["bf16"]["tensor"])
+    # the caller owns staleness: after B changes, terms computed before the change give the OLD norm
+    B_new = (mod.B.float() * 1.5).to(mod.B.dtype)
+    fresh = G.empty_f32(cfg.d_out)
+    D.dora_norm(mod.desc, mod.W, mod.A, B_new, fresh, ws)
+    stale = G.empty_f32(cfg.d_out)
+    D.dora_norm_assemble(mod.desc, terms, stale)
+    assert torch.equal(stale, c)
+    assert float((stale - fresh).abs().max() / fresh.abs().max()) > 1e-2
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_norm_terms_with_zero_scale(dtype):
+    mk = cfg_bf16 if dtype == "bf16" else cfg_f32
+    cfg = mk("s0_terms", 264, 328, 24, 8, seed=22)
+    mod = G.Module(cfg)
+    desc = D.make_desc(cfg.d_out, cfg.d_in, cfg.r, cfg.tokens, G.dtype_code(dtype), 0.0, 0.0)
+    terms, Gm, c = G.empty_f32(3, cfg.d_out), G.empty_f32(cfg.r, cfg.r), G.empty_f32(cfg.d_out)
+    D.dora_norm_terms(desc, mod.W, mod.A, mod.B, terms, Gm, G.workspace(desc, D.PHASE_NORM))
+    D.dora_norm_assemble(desc, terms, c)
+    W = mod.f64("W")
+    np.testing.assert_allclose(G.to_f64(terms[0]), np.sum(W * W, axis=1), rtol=1e-5)
+    assert float(terms[1:].abs().max()) == 0.0 and float(Gm.abs().max()) == 0.0
+    G.assert_norm_close(G.to_f64(c), np.linalg.norm(W, axis=1), G.TOL[dtype]["norm"])
+
+
 def test_norm_low_rank_terms_matter_in_stress_variant():
     # guards the guard: in the stress variant dropping BA would be far outside tolerance
     cfg = I.stress(cfg_bf16("bf16_mid", 1024, 1536, 384, 640, seed=4))
