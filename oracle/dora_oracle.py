@@ -21,6 +21,8 @@ What is defined here, and from where:
 * `backward` / `grad_*`                - Sec. 3.2 and App. C item 2: gradients of
   the compose, chained through the three linear maps, with the norm held
   constant (Sec. 2.2 last paragraph; App. A item 2 "detached").
+* `forward(x_lora=...)`, `backward_dropout` - the same with a separate input for the
+  adapter branch (LoRA dropout, App. B "Chunked dropout path").
 * `factored_norm_terms`, `assemble_norm` - the terms of Eq. (2), each from its
   definition (Eq. 3, Eq. 4), and the assembly of Eq. (5).  Not used to judge the
   HIP norm (the dense definition is); kept so the three terms can be checked one
@@ -77,15 +79,19 @@ def adapted_weight(W, A, B, m, s, eps) -> np.ndarray:
 # --------------------------------------------------------------------------- forward
 
 def forward(x, W, A, B, m, s, eps, c: Optional[np.ndarray] = None,
-            bias: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
+            bias: Optional[np.ndarray] = None, x_lora: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
     """Whole forward of one module.
 
-    base  = x W^T                  [T, d_out]
-    h     = x A^T                  [T, r]
-    lora  = h B^T                  [T, d_out]
-    inner = s*lora + base          (the tensor Tier 1 saves for backward)
-    delta = (g-1)*base + g*(s*lora)   (compose equation, App. A item 1)
+    base  = x W^T                  [T, d_out]   (what the frozen layer produces)
+    xa    = x_lora if given else x              (the adapter's input)
+    base_a = xa W^T, h = xa A^T [T, r], lora = h B^T [T, d_out]
+    inner = s*lora + base_a        (the tensor Tier 1 saves for backward)
+    delta = (g-1)*base_a + g*(s*lora)   (compose equation, App. A item 1) = xa (W' - W)^T
     y     = base + delta           (what the caller of the module ends up with)
+
+    x_lora (App. B "Chunked dropout path"): with LoRA dropout active the adapter sees the dropped
+    input while the frozen layer's output stays that of x, so the base the compose runs on is
+    recomputed for the dropped input; without dropout base_a is base.
 
     bias (App. A item 2): the frozen layer's bias is taken off its output before the
     compose and put back afterwards, i.e. it is not scaled by g: y = base + delta + bias
@@ -97,14 +103,17 @@ def forward(x, W, A, B, m, s, eps, c: Optional[np.ndarray] = None,
         c = dense_row_norm(W, A, B, s)
     g = mag_scale(m, c, eps)
     base = x @ W.T
-    h = x @ A.T
+    xa = x if x_lora is None else _f64(x_lora)
+    base_a = base if x_lora is None else xa @ W.T
+    h = xa @ A.T
     lora = h @ B.T
-    inner = s * lora + base
-    delta = (g - 1.0)[None, :] * base + g[None, :] * (s * lora)
+    inner = s * lora + base_a
+    delta = (g - 1.0)[None, :] * base_a + g[None, :] * (s * lora)
     y = base + delta
     if bias is not None:
         y = y + _f64(bias)[None, :]
-    return {"c": c, "g": g, "base": base, "h": h, "lora": lora, "inner": inner, "delta": delta, "y": y}
+    return {"c": c, "g": g, "base": base, "base_a": base_a, "h": h, "lora": lora, "inner": inner, "delta": delta,
+            "y": y}
 
 
 def compose_delta(base, lora, g, s) -> np.ndarray:
@@ -179,6 +188,32 @@ def backward(dy, x, W, A, B, m, s, eps, c=None) -> Dict[str, np.ndarray]:
         "dA": grad_A(dy, x, W, A, B, m, s, eps, c),
         "dB": grad_B(dy, x, W, A, B, m, s, eps, c),
         "dm": grad_m(dy, x, W, A, B, m, s, eps, c),
+    }
+
+
+def backward_dropout(dy, x, x_lora, W, A, B, m, s, eps, c=None) -> Dict[str, np.ndarray]:
+    """Gradients of y = x W^T + delta(x_lora) (the forward with a separate adapter input), norm constant.
+
+    The frozen path gives dx = dy W.  The adapter path: base_a = x_lora W^T receives (g-1) dy and
+    lora receives g s dy, so dx_lora = ((g-1) dy) W + dh A with dh = (g s dy) B; dA = dh^T x_lora;
+    dB = (g s dy)^T h with h = x_lora A^T; dm = (sum_t dy * inner) / max(c, eps) with
+    inner = s lora + base_a.
+    """
+    dy, x, xa, W, A, B, m = _f64(dy), _f64(x), _f64(x_lora), _f64(W), _f64(A), _f64(B), _f64(m)
+    if c is None:
+        c = dense_row_norm(W, A, B, s)
+    g = mag_scale(m, c, eps)
+    d_lora = g[None, :] * F64(s) * dy
+    d_base_a = (g - 1.0)[None, :] * dy
+    h = xa @ A.T
+    dh = d_lora @ B
+    inner = F64(s) * (h @ B.T) + xa @ W.T
+    return {
+        "dx": dy @ W,
+        "dx_lora": d_base_a @ W + dh @ A,
+        "dA": dh.T @ xa,
+        "dB": d_lora.T @ h,
+        "dm": np.sum(dy * inner, axis=0) / np.maximum(_f64(c), F64(eps)),
     }
 
 

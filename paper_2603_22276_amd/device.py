@@ -16,11 +16,11 @@ DEV = "cuda:0"
 
 
 def dtype_code(dtype: str) -> int:
-    return {"f32": D.DORA_F32, "bf16": D.DORA_BF16}[dtype]
+    return {"f32": D.DORA_F32, "bf16": D.DORA_BF16, "f16": D.DORA_F16}[dtype]
 
 
 def torch_dtype(dtype: str):
-    return {"f32": torch.float32, "bf16": torch.bfloat16}[dtype]
+    return {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[dtype]
 
 
 def to_dev(a: np.ndarray) -> torch.Tensor:

@@ -15,6 +15,8 @@ Storage conventions
 * dtype "f32": arrays are numpy float32.
 * dtype "bf16": arrays are numpy uint16 holding bfloat16 bit patterns
   (round-to-nearest-even from float32).  `to_f64` widens either form exactly.
+* dtype "f16": arrays are numpy float16 (IEEE binary16, round-to-nearest-even,
+  overflow to infinity beyond 65504).
 * m is always float32.  s is a float32 scalar (rsLoRA: alpha / sqrt(r)).
 """
 from __future__ import annotations
@@ -25,7 +27,7 @@ from typing import Dict
 import numpy as np
 
 BASE_SEED = 260322276
-TENSOR_IDS = {"W": 0, "A": 1, "B": 2, "m": 3, "x": 4, "dy": 5}
+TENSOR_IDS = {"W": 0, "A": 1, "B": 2, "m": 3, "x": 4, "dy": 5, "mask": 6}
 
 
 @dataclass(frozen=True)
@@ -37,7 +39,7 @@ class DoraConfig:
     d_in: int
     r: int
     tokens: int
-    dtype: str  # "f32" | "bf16"
+    dtype: str  # "f32" | "bf16" | "f16"
     alpha: float  # s = alpha / sqrt(r)
     sigma_B: float  # std of B entries
     sigma_m: float = 1e-3  # std of the relative jitter on m
@@ -119,6 +121,9 @@ def quantise(a64: np.ndarray, dtype: str) -> np.ndarray:
         return np.ascontiguousarray(a64, dtype=np.float32)
     if dtype == "bf16":
         return f32_to_bf16_bits(np.asarray(a64, dtype=np.float32))
+    if dtype == "f16":
+        with np.errstate(over="ignore"):
+            return np.ascontiguousarray(np.asarray(a64, dtype=np.float32).astype(np.float16))
     raise ValueError(f"unknown dtype {dtype!r}")
 
 
@@ -135,6 +140,15 @@ def _normal(seed: int, shape, std: float) -> np.ndarray:
     if std != 1.0:
         out *= np.float32(std)
     return out
+
+
+def dropped_input(cfg: DoraConfig, x: np.ndarray, p: float) -> np.ndarray:
+    """The adapter branch's input under LoRA dropout with probability p: x (.) keep / (1 - p), keep drawn
+    from the tensor's own Philox stream, rounded once to the storage dtype.  Dropout itself is outside the
+    module: its random numbers reach both the oracle and the HIP path as this input."""
+    rng = np.random.Generator(np.random.Philox(BASE_SEED + cfg.seed_offset + TENSOR_IDS["mask"]))
+    keep = rng.random(size=x.shape, dtype=np.float32) >= np.float32(p)
+    return quantise(to_f64(x) * keep / (1.0 - p), cfg.dtype)
 
 
 def make_inputs(cfg: DoraConfig, with_dy: bool = True) -> Dict[str, np.ndarray]:

@@ -357,3 +357,87 @@ def test_bias_is_re_added_unscaled():
     assert np.max(np.abs(f["y"] - wrong)) > 1e-3
     # inner is the bias-free pre-scale activation
     np.testing.assert_allclose(f["inner"], x @ (W + s * B @ A).T, rtol=1e-12, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------- LoRA dropout (App. B)
+
+def test_dropout_forward_is_the_weight_delta_applied_to_the_dropped_input():
+    # y = x W^T + x_d (W' - W)^T with W' from Eq. 1: the adapter sees the dropped input, the frozen
+    # layer's output is that of x; with x_d = x this is the plain forward
+    x, W, A, B, m, s, dy = small_problem(20, T=6, d_out=7, d_in=8, r=3, s=0.9)
+    rng = np.random.default_rng(21)
+    x_d = x * (rng.random(x.shape) >= 0.25) / 0.75
+    f = O.forward(x, W, A, B, m, s, 1e-12, x_lora=x_d)
+    Wp = O.adapted_weight(W, A, B, m, s, 1e-12)
+    np.testing.assert_allclose(f["y"], x @ W.T + x_d @ (Wp - W).T, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(f["delta"], x_d @ (Wp - W).T, rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(f["inner"], x_d @ (W + s * B @ A).T, rtol=1e-12, atol=1e-13)
+    plain = O.forward(x, W, A, B, m, s, 1e-12)
+    same = O.forward(x, W, A, B, m, s, 1e-12, x_lora=x.copy())
+    for k in ("y", "delta", "inner", "h"):
+        np.testing.assert_allclose(same[k], plain[k], rtol=1e-13, atol=1e-14)
+
+
+def test_dropout_gradients_match_finite_differences():
+    x, W, A, B, m, s, dy = small_problem(22, T=4, d_out=5, d_in=6, r=3, s=1.1)
+    rng = np.random.default_rng(23)
+    x_d = x * (rng.random(x.shape) >= 0.3) / 0.7
+    c0 = O.dense_row_norm(W, A, B, s)
+
+    def loss():
+        return float(np.sum(dy * O.forward(x, W, A, B, m, s, 1e-12, c=c0, x_lora=x_d)["y"]))
+
+    b = O.backward_dropout(dy, x, x_d, W, A, B, m, s, 1e-12)
+    for name, arr in (("dx", x), ("dx_lora", x_d), ("dA", A), ("dB", B), ("dm", m)):
+        fd = _fd(loss, arr)
+        assert np.max(np.abs(fd - b[name])) <= 1e-7 * np.max(np.abs(fd)), name
+    # without dropout the two input gradients add up to the plain module's dx
+    b0 = O.backward_dropout(dy, x, x, W, A, B, m, s, 1e-12)
+    plain = O.backward(dy, x, W, A, B, m, s, 1e-12)
+    np.testing.assert_allclose(b0["dx"] + b0["dx_lora"], plain["dx"], rtol=1e-12, atol=1e-13)
+    for k in ("dA", "dB", "dm"):
+        np.testing.assert_allclose(b0[k], plain[k], rtol=1e-12, atol=1e-13)
+
+
+# ----------------------------------------------------------------------------- fp16 storage (App. B "Dtype-aware epsilon")
+
+def test_fp16_storage_rounding_epsilon_and_saturation():
+    from paper_2603_22276_amd import inputs as I
+    q = lambda v: float(I.quantise(np.array([v], np.float64), "f16")[0])
+    # IEEE binary16, ties to even: 1 + 2^-11 is halfway between 1 and 1 + 2^-10
+    assert q(1 + 2.0 ** -11) == 1.0 and q(1 + 3 * 2.0 ** -11) == 1 + 2.0 ** -9
+    assert q(65504.0) == 65504.0 and q(65519.0) == 65504.0 and np.isinf(q(65520.0))   # largest finite value
+    assert q(2.0 ** -24) == 2.0 ** -24 and q(2.0 ** -26) == 0.0                        # subnormals kept, then zero
+    cfg = I.DoraConfig("h", 8, 16, 8, 4, "f16", 32.0, 1e-3)
+    assert cfg.eps == 1e-6                                                             # same guard as bf16
+    a = I.make_inputs(cfg)
+    assert a["W"].dtype == np.float16 and a["x"].dtype == np.float16 and a["m"].dtype == np.float32
+    assert np.array_equal(I.to_f64(a["W"]), a["W"].astype(np.float64))
+    # with eps = 1e-6 a vanishing row gives g = m / eps ~ 1e6 m: beyond fp16's range, which is why g (and the
+    # norm) are carried in fp32; in fp16 the quotient would already be infinite for m = 1
+    g = O.mag_scale(np.array([1.0, 0.05]), np.array([0.0, 0.0]), cfg.eps)
+    np.testing.assert_allclose(g, [1e6, 5e4], rtol=1e-12)
+    with np.errstate(over="ignore"):
+        assert np.isinf(np.float16(g[0])) and np.isfinite(np.float16(g[1]))
+    assert np.isfinite(np.float32(g[0]))
+
+
+def test_fp16_compose_needs_fp32_arithmetic_near_unity_g():
+    # Sec. 3.1: evaluated in fp16, (g - 1) (.) base vanishes whenever |g - 1| < 2^-11 (g rounds to 1);
+    # fp32 arithmetic with one rounding at the store keeps the correction
+    rng = np.random.default_rng(12)
+    f16 = lambda a: np.asarray(a, np.float32).astype(np.float16).astype(np.float64)
+    base = f16(rng.standard_normal((32, 256)))
+    lora = f16(rng.standard_normal((32, 256)) * 0.02)
+    g = 1 + 0.0015 * rng.standard_normal(256)
+    s = 1.633
+    exact = O.compose_delta(base, lora, g, s)
+    collapse = (g - 1 < 2.0 ** -11) & (g - 1 > -(2.0 ** -12))   # fp16 spacing is 2^-10 above 1 and 2^-11 below
+    assert 0.1 < collapse.mean() < 0.4          # a sizeable share of the rows, as the paper observes for fp16
+    g16 = f16(g)
+    in_fp16 = f16(f16((g16 - 1.0)[None, :] * base) + f16(g16[None, :] * f16(s * lora)))
+    in_fp32 = f16(np.float32(g - 1)[None, :].astype(np.float64) * base + np.float32(g)[None, :].astype(np.float64) * (s * lora))
+    assert np.all((g16 - 1.0)[collapse] == 0.0)
+    err16 = np.max(np.abs(in_fp16 - exact)[:, collapse])
+    err32 = np.max(np.abs(in_fp32 - exact)[:, collapse])
+    assert err32 < 0.2 * err16
