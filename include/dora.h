@@ -8,10 +8,14 @@
  *   - All tensor pointers are DEVICE pointers owned by the caller.  Row-major,
  *     contiguous, 16-byte aligned.  Inputs are const and never modified.
  *   - `dtype` selects the storage type of W, A, B, x, y, dy, dx, saved_h,
- *     saved_inner, base, lora: DORA_BF16 (bfloat16) or DORA_F32.  Accumulation is
- *     always fp32.  w_norm, m, g, gm1, dm, dA, dB are fp32 for either dtype.
- *   - Shape limits: d_out, d_in multiples of 8; r a multiple of 8 (bf16) or >= 1
- *     (fp32: d_out, d_in, r multiples of 4); tokens >= 0 (0 is a no-op that still
+ *     saved_inner, base, lora: DORA_BF16 (bfloat16), DORA_F16 (IEEE binary16) or
+ *     DORA_F32.  Accumulation is always fp32.  w_norm, m, g, gm1, dm, dA, dB are
+ *     fp32 for every dtype.  DORA_F16 (App. B "Dtype-aware epsilon"): eps defaults
+ *     to 1e-6 as for bf16; a value beyond 65504 in magnitude becomes an infinity
+ *     when it is stored (IEEE conversion, no clamping), which is why g and the norm
+ *     are never held in fp16.
+ *   - Shape limits: d_out, d_in, r multiples of 8 (bf16, fp16) or of 4 (fp32);
+ *     tokens >= 0 (0 is a no-op that still
  *     computes weight-only results); every tensor below 2^31 elements.
  *   - `ws` is caller-provided scratch of at least dora_workspace_bytes(desc,
  *     phase) bytes, 256-byte aligned.  The library allocates no device memory,
@@ -34,7 +38,7 @@
 extern "C" {
 #endif
 
-typedef enum { DORA_F32 = 0, DORA_BF16 = 1 } dora_dtype;
+typedef enum { DORA_F32 = 0, DORA_BF16 = 1, DORA_F16 = 2 } dora_dtype;
 
 typedef enum {
     DORA_OK = 0,
@@ -50,7 +54,7 @@ typedef struct {
     int64_t d_out, d_in, r, tokens;
     int32_t dtype; /* dora_dtype */
     float s;       /* LoRA scaling, e.g. rsLoRA alpha / sqrt(r) */
-    float eps;     /* guard of Eq. 6; <= 0 selects the default of App. A item 2: 1e-12 (F32), 1e-6 (BF16) */
+    float eps;     /* guard of Eq. 6; <= 0 selects the default of App. A item 2: 1e-12 (F32), 1e-6 (BF16, F16) */
 } dora_desc;
 
 typedef enum {
@@ -190,7 +194,7 @@ dora_status dora_forward(const dora_desc* desc, const void* x, const void* W, co
  * contraction  inner = [s*h | x] [B | W]^T  (the h = x A^T product writes both h and s*h from its
  * accumulators) whose epilogue writes y = g (.) inner (+ bias) and, if asked, inner.
  * The cancellation issue of Sec. 3.1 concerns the *delta* form only; g (.) inner taken from an fp32
- * accumulator has none.  DORA_BF16 descs only (DORA_ERR_DTYPE otherwise).  Arguments, workspace
+ * accumulator has none.  DORA_BF16 and DORA_F16 descs only (DORA_ERR_DTYPE otherwise).  Arguments, workspace
  * (DORA_PHASE_FORWARD) and saved tensors exactly as for dora_forward.
  */
 dora_status dora_forward_fused(const dora_desc* desc, const void* x, const void* W, const void* A,

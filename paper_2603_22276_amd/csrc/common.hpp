@@ -36,6 +36,46 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_hw_t));
 }
 
+// ---- the two 16-bit storage types --------------------------------------------------------------
+// Kernels that serve both take a DT template parameter; everything element-specific goes through
+// Elem16<DT>: widening a packed pair, packing two fp32 with one rounding (nearest-even; fp16 overflows
+// to infinity), and the matching MFMA.
+enum { DT_BF16 = 0, DT_F16 = 1 };
+struct f16_t { uint16_t bits; };  // distinct C++ type for fp16 storage (bf16_t is a plain uint16_t)
+typedef _Float16 f16x2_hw_t __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+
+template <int DT> struct Elem16;
+template <> struct Elem16<DT_BF16> {
+    static __device__ __forceinline__ float lo(uint32_t packed) { return bf16_lo(packed); }
+    static __device__ __forceinline__ float hi(uint32_t packed) { return bf16_hi(packed); }
+    static __device__ __forceinline__ uint32_t pack2(float a, float b) { return pack_bf16x2(a, b); }
+    static __device__ __forceinline__ f32x16_t mfma(bf16x8_t a, bf16x8_t b, f32x16_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
+};
+template <> struct Elem16<DT_F16> {
+    static __device__ __forceinline__ float lo(uint32_t packed)
+    {
+        return (float)__builtin_bit_cast(f16x2_hw_t, packed)[0];
+    }
+    static __device__ __forceinline__ float hi(uint32_t packed)
+    {
+        return (float)__builtin_bit_cast(f16x2_hw_t, packed)[1];
+    }
+    static __device__ __forceinline__ uint32_t pack2(float a, float b)
+    {
+        f32x2_hw_t v = {a, b};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2_hw_t));
+    }
+    static __device__ __forceinline__ f32x16_t mfma(bf16x8_t a, bf16x8_t b, f32x16_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0,
+                                                      0);
+    }
+};
+
 // ---- kernel timing hook (see dora_trace_* in dora_measure.h) ------------------------------------------
 void trace_begin(int kernel_id, hipStream_t stream);
 void trace_end(int kernel_id, hipStream_t stream);
@@ -76,6 +116,7 @@ struct GemmArgs {
     int64_t ldc;
     int ksplit;                // split of segment 0's K range (nseg must be 1 when > 1)
     int tag;                   // 0 or 1: selects a differently named (otherwise identical) kernel instance
+    int dt;                    // DT_BF16 or DT_F16: element type of both operands, of a 16-bit C and of rowdot / colbias
     const float* colscale;     // EPI_COMPOSE: [N] fp32
     const bf16_t* colbias;     // EPI_COMPOSE: [N] bf16 added to the scaled output, or nullptr
     void* c2;                  // second output [M, ldc] bf16 or nullptr: the unscaled accumulator (compose epilogue),
@@ -125,11 +166,13 @@ int compose_bwd_slabs(int64_t tokens, int d_out, int dtype);
 hipError_t launch_compose_bwd(int dtype, const void* dy, const void* inner, const float* g, void* dz,
                               float* partial /* [slabs][d_out] or nullptr */, int64_t tokens, int d_out, hipStream_t st);
 hipError_t launch_dm_final(const float* partial, int slabs, const float* c, float eps, float* dm, int d_out, hipStream_t st);
-hipError_t launch_gram_reduce(const float* partials, int ksplit, int r, float* G, bf16_t* Ghi, bf16_t* Glo, hipStream_t st);
+// G = sum of partials; Ghi + Glo ~ G as two 16-bit terms of element type dt (both may be nullptr)
+hipError_t launch_gram_reduce(const float* partials, int ksplit, int r, float* G, bf16_t* Ghi, bf16_t* Glo, int dt,
+                              hipStream_t st);
 // c and / or terms ([3, d_out]: the summed base_sq, cross, ba_sq) may be nullptr
 hipError_t launch_norm_final(const float* base_sq_p, int n_base, const float* cross_p, int n_cross, const float* ba_p,
                              int n_ba, double s, float* c, float* terms, int d_out, hipStream_t st);
-hipError_t launch_rownorm_s0_bf16(const bf16_t* W, float* c, int d_out, int d_in, bool squared, hipStream_t st);
+hipError_t launch_rownorm_s0_16(const bf16_t* W, int dt, float* c, int d_out, int d_in, bool squared, hipStream_t st);
 // fp32 path: base_sq, cross, ba_sq and Eq. 5 from W, B, U = W A^T, BG = B G (all fp32)
 hipError_t launch_rownorm_f32(const float* W, const float* base_in, const float* B, const float* U, const float* BG,
                               double s, float* c, float* terms, int d_out, int d_in, int r, bool squared, hipStream_t st);

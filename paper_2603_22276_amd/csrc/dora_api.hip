@@ -81,14 +81,16 @@ namespace {
 constexpr int64_t MAX_ELEMS = (int64_t)1 << 31;
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
-inline size_t esize(int dtype) { return dtype == DORA_BF16 ? 2 : 4; }
+inline size_t esize(int dtype) { return dtype == DORA_F32 ? 4 : 2; }
+inline bool is16(int dtype) { return dtype != DORA_F32; }
+inline int dt_of(int dtype) { return dtype == DORA_F16 ? DT_F16 : DT_BF16; }
 inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 dora_status check_desc(const dora_desc* d, bool need_weights)
 {
     if (!d) return DORA_ERR_NULL;
-    if (d->dtype != DORA_F32 && d->dtype != DORA_BF16) return DORA_ERR_DTYPE;
-    const int64_t mult = d->dtype == DORA_BF16 ? 8 : 4;
+    if (d->dtype != DORA_F32 && d->dtype != DORA_BF16 && d->dtype != DORA_F16) return DORA_ERR_DTYPE;
+    const int64_t mult = is16(d->dtype) ? 8 : 4;
     if (d->d_out < mult || d->d_out % mult) return DORA_ERR_SHAPE;
     if (d->tokens < 0) return DORA_ERR_SHAPE;
     if (d->tokens * d->d_out >= MAX_ELEMS) return DORA_ERR_SHAPE;
@@ -103,7 +105,7 @@ dora_status check_desc(const dora_desc* d, bool need_weights)
     return DORA_OK;
 }
 
-inline float eff_eps(const dora_desc* d) { return d->eps > 0.f ? d->eps : (d->dtype == DORA_BF16 ? 1e-6f : 1e-12f); }
+inline float eff_eps(const dora_desc* d) { return d->eps > 0.f ? d->eps : (is16(d->dtype) ? 1e-6f : 1e-12f); }
 
 #define DORA_REQ_PTR(p)                          \
     do {                                         \
@@ -171,7 +173,7 @@ void plan_norm(const dora_desc* d, Bump& b, NormPlan& n)
     if (n.ks_g > 16) n.ks_g = 16;
     if (n.ks_g > ktiles) n.ks_g = ktiles;
     if (n.ks_g < 1) n.ks_g = 1;
-    if (d->dtype == DORA_BF16) {
+    if (is16(d->dtype)) {
         n.base_p = b.take<float>((size_t)n.ks_u * d->d_out);
         n.cross_p = b.take<float>((size_t)n.ks_u * n.tiles_n * d->d_out);
         n.ba_p = b.take<float>((size_t)n.tiles_n * d->d_out);
@@ -189,8 +191,8 @@ void plan_norm(const dora_desc* d, Bump& b, NormPlan& n)
 // one contraction, either dtype
 struct Seg { const void* a; int64_t lda; const void* b; int64_t ldb; int K; };
 
-GemmArgs bf16_args(bool a_kc, bool b_kc, int M, int N, const Seg* segs, int nseg, float alpha, void* c, int64_t ldc,
-                   bool c_f32, int tag)
+GemmArgs bf16_args(int dt, bool a_kc, bool b_kc, int M, int N, const Seg* segs, int nseg, float alpha, void* c,
+                   int64_t ldc, bool c_f32, int tag)
 {
     GemmArgs g;
     memset(&g, 0, sizeof(g));
@@ -198,16 +200,16 @@ GemmArgs bf16_args(bool a_kc, bool b_kc, int M, int N, const Seg* segs, int nseg
         g.seg[i] = GemmSeg{(const bf16_t*)segs[i].a, (const bf16_t*)segs[i].b, segs[i].lda, segs[i].ldb, segs[i].K};
     g.nseg = nseg; g.M = M; g.N = N; g.a_kcontig = a_kc; g.b_kcontig = b_kc;
     g.epilogue = c_f32 ? EPI_STORE_F32 : EPI_STORE_BF16;
-    g.alpha = alpha; g.c = c; g.ldc = ldc; g.ksplit = 1; g.tag = tag;
+    g.alpha = alpha; g.c = c; g.ldc = ldc; g.ksplit = 1; g.tag = tag; g.dt = dt;
     return g;
 }
 
 hipError_t contract(int dtype, bool a_kc, bool b_kc, int M, int N, const Seg* segs, int nseg, float alpha, void* c,
                     int64_t ldc, bool c_f32, int trace_id, hipStream_t st)
 {
-    if (dtype == DORA_BF16) {
+    if (is16(dtype)) {
         const int tag = (trace_id == DORA_K_GEMM_LORA || trace_id == DORA_K_GEMM_DB) ? 1 : 0;
-        return launch_gemm_bf16(bf16_args(a_kc, b_kc, M, N, segs, nseg, alpha, c, ldc, c_f32, tag), trace_id, st);
+        return launch_gemm_bf16(bf16_args(dt_of(dtype), a_kc, b_kc, M, N, segs, nseg, alpha, c, ldc, c_f32, tag), trace_id, st);
     }
     SgemmArgs g;
     memset(&g, 0, sizeof(g));
@@ -232,9 +234,9 @@ dora_status norm_impl(const dora_desc* d, const void* W, const void* A, const vo
     const int d_out = (int)d->d_out, d_in = (int)d->d_in, r = (int)d->r;
     if (d->s == 0.f) {  // scale-is-zero fast path: no U, no G
         if (terms) {  // base_sq from W (or the cache), cross = ba_sq = 0, G not formed
-            if (G_out) DORA_HIP(launch_gram_reduce(nullptr, 0, r, G_out, nullptr, nullptr, st));  // zero partials: G = 0
-            if (!base_sq && d->dtype == DORA_BF16) {
-                DORA_HIP(launch_rownorm_s0_bf16((const bf16_t*)W, n.base_p, d_out, d_in, true, st));
+            if (G_out) DORA_HIP(launch_gram_reduce(nullptr, 0, r, G_out, nullptr, nullptr, DT_BF16, st));  // zero partials: G = 0
+            if (!base_sq && is16(d->dtype)) {
+                DORA_HIP(launch_rownorm_s0_16((const bf16_t*)W, dt_of(d->dtype), n.base_p, d_out, d_in, true, st));
                 base_sq = n.base_p;
             }
             if (base_sq) DORA_HIP(launch_norm_final(base_sq, 1, nullptr, 0, nullptr, 0, 0.0, c, terms, d_out, st));
@@ -242,32 +244,33 @@ dora_status norm_impl(const dora_desc* d, const void* W, const void* A, const vo
             return DORA_OK;
         }
         if (base_sq) DORA_HIP(launch_norm_final(base_sq, 1, nullptr, 0, nullptr, 0, 0.0, c, nullptr, d_out, st));
-        else if (d->dtype == DORA_BF16) DORA_HIP(launch_rownorm_s0_bf16((const bf16_t*)W, c, d_out, d_in, false, st));
+        else if (is16(d->dtype)) DORA_HIP(launch_rownorm_s0_16((const bf16_t*)W, dt_of(d->dtype), c, d_out, d_in, false, st));
         else DORA_HIP(launch_rownorm_f32((const float*)W, nullptr, nullptr, nullptr, nullptr, 0.0, c, nullptr, d_out, d_in, r, false, st));
         return DORA_OK;
     }
-    if (d->dtype == DORA_BF16) {
+    if (is16(d->dtype)) {
+        const int dt = dt_of(d->dtype);
         GemmArgs g;
         // cross term (Eq. 3) and base term: U = W A^T tile by tile, reduced against B in registers
         memset(&g, 0, sizeof(g));
         g.seg[0] = GemmSeg{(const bf16_t*)W, (const bf16_t*)A, d_in, d_in, d_in};
-        g.nseg = 1; g.M = d_out; g.N = r; g.a_kcontig = 1; g.b_kcontig = 1; g.epilogue = EPI_ROWDOT; g.alpha = 1.f;
+        g.nseg = 1; g.M = d_out; g.N = r; g.a_kcontig = 1; g.b_kcontig = 1; g.epilogue = EPI_ROWDOT; g.alpha = 1.f; g.dt = dt;
         g.ksplit = n.ks_u; g.rowdot = (const bf16_t*)B; g.ld_rowdot = r; g.rowdot_partial = n.cross_p;
         g.base_sq_partial = base_sq ? nullptr : n.base_p;
         DORA_HIP(launch_gemm_bf16(g, DORA_K_NORM_CROSS, st));
         // Gram matrix (Eq. 4): split-K partials, then a fixed-order sum and the hi/lo bf16 expansion
         memset(&g, 0, sizeof(g));
         g.seg[0] = GemmSeg{(const bf16_t*)A, (const bf16_t*)A, d_in, d_in, d_in};
-        g.nseg = 1; g.M = r; g.N = r; g.a_kcontig = 1; g.b_kcontig = 1; g.epilogue = EPI_STORE_F32; g.alpha = 1.f;
+        g.nseg = 1; g.M = r; g.N = r; g.a_kcontig = 1; g.b_kcontig = 1; g.epilogue = EPI_STORE_F32; g.alpha = 1.f; g.dt = dt;
         g.c = n.gram_p; g.ldc = r; g.ksplit = n.ks_g;
         DORA_HIP(launch_gemm_bf16(g, DORA_K_GRAM, st));
-        DORA_HIP(launch_gram_reduce(n.gram_p, n.ks_g, r, G_out, n.Ghi, n.Glo, st));
+        DORA_HIP(launch_gram_reduce(n.gram_p, n.ks_g, r, G_out, n.Ghi, n.Glo, dt, st));
         // BA-norm term: rowdot(B, B G) with G = Ghi + Glo kept to ~16 mantissa bits (G is symmetric,
         // so G serves as its own K-contiguous N-side operand)
         memset(&g, 0, sizeof(g));
         g.seg[0] = GemmSeg{(const bf16_t*)B, n.Ghi, r, r, r};
         g.seg[1] = GemmSeg{(const bf16_t*)B, n.Glo, r, r, r};
-        g.nseg = 2; g.M = d_out; g.N = r; g.a_kcontig = 1; g.b_kcontig = 1; g.epilogue = EPI_ROWDOT; g.alpha = 1.f;
+        g.nseg = 2; g.M = d_out; g.N = r; g.a_kcontig = 1; g.b_kcontig = 1; g.epilogue = EPI_ROWDOT; g.alpha = 1.f; g.dt = dt;
         g.ksplit = 1; g.rowdot = (const bf16_t*)B; g.ld_rowdot = r; g.rowdot_partial = n.ba_p; g.tag = 1;
         DORA_HIP(launch_gemm_bf16(g, DORA_K_BA_SQ, st));
         DORA_HIP(launch_norm_final(base_sq ? base_sq : n.base_p, base_sq ? 1 : n.ks_u, n.cross_p, n.ks_u * n.tiles_n,
@@ -431,12 +434,12 @@ dora_status dora_base_sq(const dora_desc* desc, const void* W, float* base_sq, v
 {
     dora_status st = check_desc(desc, false);
     if (st != DORA_OK) return st;
-    const int64_t mult = desc->dtype == DORA_BF16 ? 8 : 4;
+    const int64_t mult = is16(desc->dtype) ? 8 : 4;
     if (desc->d_in < mult || desc->d_in % mult || desc->d_out * desc->d_in >= MAX_ELEMS) return DORA_ERR_SHAPE;
     DORA_REQ_PTR(W); DORA_REQ_PTR(base_sq);
     const int d_out = (int)desc->d_out, d_in = (int)desc->d_in;
     hipStream_t s = (hipStream_t)stream;
-    if (desc->dtype == DORA_BF16) DORA_HIP(launch_rownorm_s0_bf16((const bf16_t*)W, base_sq, d_out, d_in, true, s));
+    if (is16(desc->dtype)) DORA_HIP(launch_rownorm_s0_16((const bf16_t*)W, dt_of(desc->dtype), base_sq, d_out, d_in, true, s));
     else DORA_HIP(launch_rownorm_f32((const float*)W, nullptr, nullptr, nullptr, nullptr, 0.0, base_sq, nullptr, d_out, d_in, 0, true, s));
     return DORA_OK;
 }
@@ -584,7 +587,7 @@ dora_status dora_forward_fused(const dora_desc* desc, const void* x, const void*
 {
     dora_status st = check_desc(desc, true);
     if (st != DORA_OK) return st;
-    if (desc->dtype != DORA_BF16) return DORA_ERR_DTYPE;
+    if (!is16(desc->dtype)) return DORA_ERR_DTYPE;
     DORA_REQ_PTR(W); DORA_REQ_PTR(A); DORA_REQ_PTR(B); DORA_REQ_PTR(m);
     if (desc->tokens > 0) { DORA_REQ_PTR(x); DORA_REQ_PTR(y); }
     DORA_OPT_PTR(w_norm); DORA_OPT_PTR(bias); DORA_OPT_PTR(saved_h); DORA_OPT_PTR(saved_inner); DORA_OPT_PTR(w_norm_out);
@@ -612,12 +615,12 @@ dora_status dora_forward_fused(const dora_desc* desc, const void* x, const void*
     // the low-rank operand of the K-concatenated product  [s h | x] [B | W]^T = s h B^T + x W^T
     void* h = saved_h ? saved_h : p.h;
     Seg s1{x, d_in, A, d_in, d_in};
-    GemmArgs gh = bf16_args(true, true, T, r, &s1, 1, 1.f, h, r, false, 0);
+    GemmArgs gh = bf16_args(dt_of(desc->dtype), true, true, T, r, &s1, 1, 1.f, h, r, false, 0);
     gh.c2 = p.hs;
     gh.alpha2 = desc->s;
     DORA_HIP(launch_gemm_bf16(gh, DORA_K_GEMM_H, s));
     Seg segs[2] = {{p.hs, r, B, r, r}, {x, d_in, W, d_in, d_in}};
-    GemmArgs g = bf16_args(true, true, T, d_out, segs, 2, 1.f, y, d_out, false, 0);
+    GemmArgs g = bf16_args(dt_of(desc->dtype), true, true, T, d_out, segs, 2, 1.f, y, d_out, false, 0);
     g.epilogue = EPI_COMPOSE;
     g.colscale = p.g;
     g.colbias = (const bf16_t*)bias;
@@ -695,10 +698,10 @@ dora_status dora_backward(const dora_desc* desc, const void* dy, const void* x, 
     }
     Seg sa{p.dh, r, x, d_in, T};   // dA = dh^T x
     Seg sb{p.dz, d_out, h, r, T};  // dB = s * dz^T h
-    if (dA && dB && dt == DORA_BF16) {
+    if (dA && dB && is16(dt)) {
         // the two weight gradients are independent and individually too small to fill the chip: one launch
-        GemmArgs ga = bf16_args(false, false, r, d_in, &sa, 1, 1.f, dA, d_in, true, 0);
-        GemmArgs gb = bf16_args(false, false, d_out, r, &sb, 1, desc->s, dB, r, true, 0);
+        GemmArgs ga = bf16_args(dt_of(dt), false, false, r, d_in, &sa, 1, 1.f, dA, d_in, true, 0);
+        GemmArgs gb = bf16_args(dt_of(dt), false, false, d_out, r, &sb, 1, desc->s, dB, r, true, 0);
         DORA_HIP(launch_gemm_bf16_pair(ga, gb, DORA_K_GEMM_DA, s));
     } else {
         if (dA) DORA_HIP(contract(dt, false, false, r, d_in, &sa, 1, 1.f, dA, d_in, true, DORA_K_GEMM_DA, s));

@@ -40,6 +40,23 @@ template <> struct Vec<bf16_t> {
         return r;
     }
 };
+template <> struct Vec<f16_t> {
+    static constexpr int N = 8;
+    typedef uint4 raw_t;
+    typedef Elem16<DT_F16> E;
+    static __device__ __forceinline__ void unpack(const raw_t& r, float* f)
+    {
+        f[0] = E::lo(r.x); f[1] = E::hi(r.x); f[2] = E::lo(r.y); f[3] = E::hi(r.y);
+        f[4] = E::lo(r.z); f[5] = E::hi(r.z); f[6] = E::lo(r.w); f[7] = E::hi(r.w);
+    }
+    static __device__ __forceinline__ raw_t pack(const float* f)
+    {
+        raw_t r;
+        r.x = E::pack2(f[0], f[1]); r.y = E::pack2(f[2], f[3]);
+        r.z = E::pack2(f[4], f[5]); r.w = E::pack2(f[6], f[7]);
+        return r;
+    }
+};
 template <> struct Vec<float> {
     static constexpr int N = 4;
     typedef float4 raw_t;
@@ -85,7 +102,8 @@ __global__ void norm_final_kernel(const float* __restrict__ base_p, int n_base, 
     c[j] = __fsqrt_rn(rad);
 }
 
-// G = sum of split-K partials (fixed order), and its two-term bf16 expansion G ~ Ghi + Glo.
+// G = sum of split-K partials (fixed order), and its two-term 16-bit expansion G ~ Ghi + Glo.
+template <int DT>
 __global__ void gram_reduce_kernel(const float* __restrict__ p, int ksplit, int rr, float* __restrict__ G,
                                    bf16_t* __restrict__ Ghi, bf16_t* __restrict__ Glo)
 {
@@ -95,10 +113,11 @@ __global__ void gram_reduce_kernel(const float* __restrict__ p, int ksplit, int 
     for (int z = 0; z < ksplit; ++z) acc += p[(int64_t)z * rr + i];
     if (G) G[i] = acc;
     if (!Ghi) return;
-    uint32_t hi = f32_to_bf16_bits(acc);
-    float rem = acc - __uint_as_float(hi << 16);
+    typedef Elem16<DT> E;
+    uint32_t hi = E::pack2(acc, 0.f) & 0xffffu;
+    float rem = acc - E::lo(hi);     // exact: the leading bits of acc cancel
     Ghi[i] = (bf16_t)hi;
-    Glo[i] = (bf16_t)f32_to_bf16_bits(rem);
+    Glo[i] = (bf16_t)(E::pack2(rem, 0.f) & 0xffffu);
 }
 
 // fp32 configuration: the three terms of Eq. 2 for one row per wavefront, from U = W A^T and BG = B G.
@@ -142,19 +161,20 @@ __global__ void rownorm_f32_kernel(const float* __restrict__ W, const float* __r
     }
 }
 
-// s == 0 (Algorithm 1, notes): the norm is the row norm of W alone.  One wavefront per row, bf16 storage.
-__global__ void rownorm_s0_bf16_kernel(const bf16_t* __restrict__ W, float* __restrict__ c, int d_out, int d_in,
-                                       bool squared)
+// s == 0 (Algorithm 1, notes): the norm is the row norm of W alone.  One wavefront per row, 16-bit storage.
+template <typename T>
+__global__ void rownorm_s0_16_kernel(const T* __restrict__ W, float* __restrict__ c, int d_out, int d_in,
+                                     bool squared)
 {
     int lane = threadIdx.x & 63;
     int row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (row >= d_out) return;
-    const bf16_t* w = W + (int64_t)row * d_in;
+    const T* w = W + (int64_t)row * d_in;
     float acc = 0.f;
     for (int k = lane * 8; k < d_in; k += 64 * 8) {
         uint4 v = *reinterpret_cast<const uint4*>(w + k);
         float f[8];
-        Vec<bf16_t>::unpack(v, f);
+        Vec<T>::unpack(v, f);
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc = fmaf(f[i], f[i], acc);
     }
@@ -346,20 +366,25 @@ hipError_t launch_norm_final(const float* base_p, int n_base, const float* cross
     return hipGetLastError();
 }
 
-hipError_t launch_gram_reduce(const float* partials, int ksplit, int r, float* G, bf16_t* Ghi, bf16_t* Glo, hipStream_t st)
+hipError_t launch_gram_reduce(const float* partials, int ksplit, int r, float* G, bf16_t* Ghi, bf16_t* Glo, int dt,
+                              hipStream_t st)
 {
     int rr = r * r;
     if (rr == 0) return hipSuccess;
     TraceScope ts(DORA_K_GRAM_REDUCE, st);
-    gram_reduce_kernel<<<dim3((rr + 255) / 256), dim3(256), 0, st>>>(partials, ksplit, rr, G, Ghi, Glo);
+    if (dt == DT_F16) gram_reduce_kernel<DT_F16><<<dim3((rr + 255) / 256), dim3(256), 0, st>>>(partials, ksplit, rr, G, Ghi, Glo);
+    else gram_reduce_kernel<DT_BF16><<<dim3((rr + 255) / 256), dim3(256), 0, st>>>(partials, ksplit, rr, G, Ghi, Glo);
     return hipGetLastError();
 }
 
-hipError_t launch_rownorm_s0_bf16(const bf16_t* W, float* c, int d_out, int d_in, bool squared, hipStream_t st)
+hipError_t launch_rownorm_s0_16(const bf16_t* W, int dt, float* c, int d_out, int d_in, bool squared, hipStream_t st)
 {
     if (d_out == 0) return hipSuccess;
     TraceScope ts(DORA_K_NORM_FINAL, st);
-    rownorm_s0_bf16_kernel<<<dim3((d_out + 3) / 4), dim3(256), 0, st>>>(W, c, d_out, d_in, squared);
+    if (dt == DT_F16)
+        rownorm_s0_16_kernel<f16_t><<<dim3((d_out + 3) / 4), dim3(256), 0, st>>>((const f16_t*)W, c, d_out, d_in, squared);
+    else
+        rownorm_s0_16_kernel<bf16_t><<<dim3((d_out + 3) / 4), dim3(256), 0, st>>>(W, c, d_out, d_in, squared);
     return hipGetLastError();
 }
 
@@ -378,7 +403,7 @@ hipError_t launch_rownorm_f32(const float* W, const float* base_in, const float*
 // backward; shorter ones are chosen only when the launch would otherwise leave CUs without work.
 static int slab_rows(int preferred, int64_t tokens, int d_out, int dtype)
 {
-    const int n = dtype == DORA_BF16 ? 8 : 4;
+    const int n = dtype == DORA_F32 ? 4 : 8;
     const int64_t col_blocks = (d_out / n + CW - 1) / CW;
     for (int rows = preferred; rows > 16; rows >>= 1)
         if (col_blocks * ((tokens + rows - 1) / rows) >= 512) return rows;
@@ -416,6 +441,8 @@ hipError_t launch_compose_fwd(int dtype, const void* base, const void* lora, con
     TraceScope ts(DORA_K_COMPOSE_FWD, st);
     if (dtype == DORA_BF16)
         return compose_fwd_t<bf16_t>(base, lora, g, gm1, bias, s, out, write_delta, inner, tokens, d_out, st);
+    if (dtype == DORA_F16)
+        return compose_fwd_t<f16_t>(base, lora, g, gm1, bias, s, out, write_delta, inner, tokens, d_out, st);
     return compose_fwd_t<float>(base, lora, g, gm1, bias, s, out, write_delta, inner, tokens, d_out, st);
 }
 
@@ -452,6 +479,7 @@ hipError_t launch_compose_bwd(int dtype, const void* dy, const void* inner, cons
     if (tokens == 0 || d_out == 0) return hipSuccess;
     TraceScope ts(DORA_K_COMPOSE_BWD, st);
     if (dtype == DORA_BF16) return compose_bwd_t<bf16_t>(dy, inner, g, dz, partial, tokens, d_out, st);
+    if (dtype == DORA_F16) return compose_bwd_t<f16_t>(dy, inner, g, dz, partial, tokens, d_out, st);
     return compose_bwd_t<float>(dy, inner, g, dz, partial, tokens, d_out, st);
 }
 

@@ -1,4 +1,4 @@
-// bf16 MFMA GEMM family for gfx950 (CDNA4), fp32 accumulation.
+// 16-bit (bf16 or fp16 storage) MFMA GEMM family for gfx950 (CDNA4), fp32 accumulation.
 //
 //   C[M,N] = alpha * sum_seg sum_k Aop[m,k] * Bop[n,k]
 //
@@ -283,9 +283,11 @@ __device__ __forceinline__ void wait_lgkmcnt()
 
 // TAG takes no part in the computation: it gives the two contractions that would otherwise share an
 // instantiation separate kernel names, so that a profiler's per-kernel statistics line up with them.
-template <class T, bool A_KC, bool B_KC, int EPI, int TAG>
+// DT: element type of the operands (and of a 16-bit C, the row-dot operand and the column bias).
+template <class T, bool A_KC, bool B_KC, int EPI, int TAG, int DT>
 __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
 {
+    typedef Elem16<DT> E;
     // one launch may carry two independent problems of the same kind (e.g. dA and dB): workgroups
     // past count0 belong to the second one
     const bool second = (int)blockIdx.x >= grp.count0;
@@ -413,7 +415,7 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
                     uint32_t w[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        float lo = bf16_lo(w[e]), hi = bf16_hi(w[e]);
+                        float lo = E::lo(w[e]), hi = E::hi(w[e]);
                         bsq[i] = fmaf(lo, lo, bsq[i]);
                         bsq[i] = fmaf(hi, hi, bsq[i]);
                     }
@@ -426,7 +428,7 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
         for (int i = 0; i < MT; ++i)
 #pragma unroll
             for (int j = 0; j < NT; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+                acc[i][j] = E::mfma(bfr[j], af[i], acc[i][j]);
         base_term(af, kk);
     };
 
@@ -462,7 +464,7 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
             static_for<NM>([&](auto nt) {
                 constexpr int n = decltype(nt)::value;
                 constexpr int i = n / NT, j = n % NT;
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xb[j], xa[i], acc[i][j], 0, 0, 0);
+                acc[i][j] = E::mfma(xb[j], xa[i], acc[i][j]);
                 if constexpr (n < NF) {
                     read_frag(kk_tag, nt, na, nb, sa, sb);
                 } else {
@@ -553,7 +555,7 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
             static_for<NM>([&](auto nt) {
                 constexpr int n = decltype(nt)::value;
                 constexpr int i = n / NT, j = n % NT;
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[KC][j], fa[KC][i], acc[i][j], 0, 0, 0);
+                acc[i][j] = E::mfma(fb[KC][j], fa[KC][i], acc[i][j]);
                 if constexpr (n < NF) read_frag(kn_tag, nt, fa[KN], fb[KN], sa, sb);
                 if constexpr (LOADS) {
                     static_for<LPT / NM>([&](auto dt) {
@@ -665,10 +667,10 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
                         const int ng = n0 + wn0 + j * 32 + b * 8 + lh * 4;
                         if (ng < p.N) {
                             uint2 rv = *reinterpret_cast<const uint2*>(p.rowdot + (int64_t)mg * p.ld_rowdot + ng);
-                            rs = fmaf(acc[i][j][b * 4 + 0], bf16_lo(rv.x), rs);
-                            rs = fmaf(acc[i][j][b * 4 + 1], bf16_hi(rv.x), rs);
-                            rs = fmaf(acc[i][j][b * 4 + 2], bf16_lo(rv.y), rs);
-                            rs = fmaf(acc[i][j][b * 4 + 3], bf16_hi(rv.y), rs);
+                            rs = fmaf(acc[i][j][b * 4 + 0], E::lo(rv.x), rs);
+                            rs = fmaf(acc[i][j][b * 4 + 1], E::hi(rv.x), rs);
+                            rs = fmaf(acc[i][j][b * 4 + 2], E::lo(rv.y), rs);
+                            rs = fmaf(acc[i][j][b * 4 + 3], E::hi(rv.y), rs);
                         }
                     }
             }
@@ -722,8 +724,8 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
                         g4 = (ng < p.N) ? *reinterpret_cast<const float4*>(p.colscale + ng) : make_float4(0.f, 0.f, 0.f, 0.f);
                         if (p.colbias && ng < p.N) b4 = *reinterpret_cast<const uint2*>(p.colbias + ng);
                     }
-                    v0 = fmaf(g4.x, acc[i][j][b * 4 + 0], bf16_lo(b4.x)); v1 = fmaf(g4.y, acc[i][j][b * 4 + 1], bf16_hi(b4.x));
-                    v2 = fmaf(g4.z, acc[i][j][b * 4 + 2], bf16_lo(b4.y)); v3 = fmaf(g4.w, acc[i][j][b * 4 + 3], bf16_hi(b4.y));
+                    v0 = fmaf(g4.x, acc[i][j][b * 4 + 0], E::lo(b4.x)); v1 = fmaf(g4.y, acc[i][j][b * 4 + 1], E::hi(b4.x));
+                    v2 = fmaf(g4.z, acc[i][j][b * 4 + 2], E::lo(b4.y)); v3 = fmaf(g4.w, acc[i][j][b * 4 + 3], E::hi(b4.y));
                 } else {
                     const float al = (pass == 0) ? p.alpha : p.alpha2;
                     v0 = al * acc[i][j][b * 4 + 0]; v1 = al * acc[i][j][b * 4 + 1];
@@ -731,8 +733,8 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
                 }
                 if (OUT_BF16) {
                     uint2 o;
-                    o.x = pack_bf16x2(v0, v1);
-                    o.y = pack_bf16x2(v2, v3);
+                    o.x = E::pack2(v0, v1);
+                    o.y = E::pack2(v2, v3);
                     *reinterpret_cast<uint2*>(stg + l32 * ROW_BYTES + col * 2) = o;
                 } else {
                     *reinterpret_cast<float4*>(stg + l32 * ROW_BYTES + col * 4) = make_float4(v0, v1, v2, v3);
@@ -769,10 +771,14 @@ hipError_t launch_one(const GemmArgs& a, const GemmArgs* b, hipStream_t stream)
     grp.count0 = grid_of<T>(a);
     const int grid = grp.count0 + (b ? grid_of<T>(*b) : 0);
     if (grid == 0) return hipSuccess;
-    if (a.tag)
-        gemm_bf16_kernel<T, A_KC, B_KC, EPI, 1><<<dim3(grid), dim3(T::THREADS), 0, stream>>>(grp);
-    else
-        gemm_bf16_kernel<T, A_KC, B_KC, EPI, 0><<<dim3(grid), dim3(T::THREADS), 0, stream>>>(grp);
+    if (b && b->dt != a.dt) return hipErrorInvalidValue;
+    if (a.dt == DT_F16) {
+        if (a.tag) gemm_bf16_kernel<T, A_KC, B_KC, EPI, 1, DT_F16><<<dim3(grid), dim3(T::THREADS), 0, stream>>>(grp);
+        else gemm_bf16_kernel<T, A_KC, B_KC, EPI, 0, DT_F16><<<dim3(grid), dim3(T::THREADS), 0, stream>>>(grp);
+    } else {
+        if (a.tag) gemm_bf16_kernel<T, A_KC, B_KC, EPI, 1, DT_BF16><<<dim3(grid), dim3(T::THREADS), 0, stream>>>(grp);
+        else gemm_bf16_kernel<T, A_KC, B_KC, EPI, 0, DT_BF16><<<dim3(grid), dim3(T::THREADS), 0, stream>>>(grp);
+    }
     return hipGetLastError();
 }
 

@@ -12,8 +12,9 @@ from paper_2603_22276_amd.device import (DEV, Module, desc_of, dtype_code, empty
                                           to_dev, to_f64, workspace)
 
 # Tolerances (relative): norm <= 1e-3 and tensors <= 2e-2 for bf16 storage with fp32 accumulation,
-# 1e-5 for the fp32 configuration.
-TOL = {"bf16": {"norm": 1e-3, "tensor": 2e-2}, "f32": {"norm": 1e-5, "tensor": 1e-5}}
+# 1e-5 for the fp32 configuration.  fp16 storage rounds to 11 significant bits against bf16's 8, so its
+# tensors are held to a quarter of the bf16 bound.
+TOL = {"bf16": {"norm": 1e-3, "tensor": 2e-2}, "f16": {"norm": 1e-3, "tensor": 5e-3}, "f32": {"norm": 1e-5, "tensor": 1e-5}}
 
 
 # Achieved errors of the run, keyed by "<context>/<tensor>": written to $DORA_PARITY_LOG at exit when that

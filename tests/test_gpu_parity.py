@@ -18,8 +18,16 @@ def cfg_bf16(name, d_out, d_in, r, tokens, sigma_B=1e-3, seed=0):
     return I.DoraConfig(name, d_out, d_in, r, tokens, "bf16", 32.0, sigma_B, seed_offset=7000 + seed)
 
 
+def cfg_f16(name, d_out, d_in, r, tokens, sigma_B=1e-3, seed=0):
+    return I.DoraConfig(name, d_out, d_in, r, tokens, "f16", 32.0, sigma_B, seed_offset=7500 + seed)
+
+
 def cfg_f32(name, d_out, d_in, r, tokens, sigma_B=1e-2, seed=0):
     return I.DoraConfig(name, d_out, d_in, r, tokens, "f32", 16.0, sigma_B, seed_offset=8000 + seed)
+
+
+def mk_of(dtype):
+    return {"bf16": cfg_bf16, "f16": cfg_f16, "f32": cfg_f32}[dtype]
 
 
 SMALL = [
@@ -30,6 +38,10 @@ SMALL = [
     I.stress(cfg_bf16("bf16_mid", 1024, 1536, 384, 640, seed=4)),
     cfg_bf16("bf16_mid", 1024, 1536, 384, 640, seed=4),
     cfg_bf16("bf16_bigtile_ragged", 4104, 264, 16, 4104, sigma_B=2e-2, seed=5),
+    # fp16 storage (App. B): the same kernels with the fp16 MFMA and conversions
+    cfg_f16("f16_ragged_tiny", 200, 328, 24, 77, seed=2),
+    I.stress(cfg_f16("f16_mid", 1024, 1536, 384, 640, seed=4)),
+    cfg_f16("f16_bigtile_ragged", 4104, 264, 16, 4104, sigma_B=2e-2, seed=5),
 ]
 IDS = [c.name for c in SMALL]
 
@@ -163,9 +175,9 @@ def test_norm_low_rank_terms_matter_in_stress_variant():
     assert np.max(np.abs(only_w - ref) / ref) > 0.1
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
 def test_norm_special_cases(dtype):
-    mk = cfg_bf16 if dtype == "bf16" else cfg_f32
+    mk = mk_of(dtype)
     cfg = mk("special", 264, 200, 16, 8, seed=6)
     inp = I.make_inputs(cfg)
     tol = G.TOL[dtype]["norm"]
@@ -199,7 +211,7 @@ def test_norm_nan_propagates():
 
 # ----------------------------------------------------------------------------- g (a6)
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
 def test_mag_scale(dtype):
     rng = np.random.default_rng(1)
     n = 1000
@@ -207,7 +219,7 @@ def test_mag_scale(dtype):
     c[:3] = [0.0, 1e-9, 1e-20]
     m = (c.astype(np.float64) * (1 + 1e-3 * rng.standard_normal(n))).astype(np.float32)
     m[:3] = 1.0
-    eps = 1e-6 if dtype == "bf16" else 1e-12
+    eps = 1e-12 if dtype == "f32" else 1e-6
     desc = D.make_desc(n, 8, 8, 0, G.dtype_code(dtype), 1.0)
     g, gm1 = G.empty_f32(n), G.empty_f32(n)
     D.dora_mag_scale(desc, G.to_dev(m), G.to_dev(c), g, gm1)
@@ -220,7 +232,8 @@ def test_mag_scale(dtype):
 # ----------------------------------------------------------------------------- compose forward (a9)
 
 @pytest.mark.parametrize("dtype,tokens,d_out", [("f32", 64, 256), ("f32", 33, 100), ("bf16", 77, 200),
-                                               ("bf16", 300, 2056), ("bf16", 1, 8), ("bf16", 1030, 4096)])
+                                               ("bf16", 300, 2056), ("bf16", 1, 8), ("bf16", 1030, 4096),
+                                               ("f16", 77, 200), ("f16", 1030, 4096)])
 def test_compose_forward(dtype, tokens, d_out):
     rng = np.random.default_rng(tokens * 7 + d_out)
     base_s = I.quantise(rng.standard_normal((tokens, d_out)), dtype)
@@ -272,10 +285,33 @@ def test_compose_forward_stable_near_unity():
     assert np.all(err <= 2.0 ** -8 * np.abs(ref) + 1e-30)
 
 
+def test_fp16_store_overflows_to_infinity_like_the_ieee_conversion():
+    # App. B "Dtype-aware epsilon": fp16 ends at 65504.  A result beyond it becomes an infinity when it is
+    # stored, exactly as the IEEE conversion of the oracle's value does; nothing is clamped, and the
+    # elements around it are untouched.
+    tokens, d_out = 16, 64
+    base64 = np.full((tokens, d_out), 100.0)
+    base64[3, 5], base64[4, 6], base64[7, 9] = 60000.0, -60000.0, 65000.0
+    base_s, lora_s = I.quantise(base64, "f16"), I.quantise(np.zeros((tokens, d_out)), "f16")
+    g32 = np.full(d_out, 1.2, np.float32)
+    g32[9] = 1.0
+    desc = D.make_desc(d_out, 8, 8, tokens, D.DORA_F16, 1.0)
+    out = G.empty((tokens, d_out), "f16")
+    D.dora_compose(desc, G.to_dev(base_s), G.to_dev(lora_s), G.to_dev(g32), None, out, 0, None)
+    ref = I.to_f64(base_s) + O.compose_delta(I.to_f64(base_s), I.to_f64(lora_s), g32.astype(np.float64), 1.0)
+    ref16 = I.to_f64(I.quantise(ref, "f16"))
+    got = G.to_f64(out)
+    assert got[3, 5] == np.inf and got[4, 6] == -np.inf and got[7, 9] == 65000.0 - 8.0   # 65000 rounds to 64992
+    assert np.array_equal(np.isinf(got), np.isinf(ref16))
+    fin = np.isfinite(ref16)
+    assert np.max(np.abs(got[fin] - ref[fin]) / np.abs(ref[fin])) <= 2.0 ** -11
+
+
 # ----------------------------------------------------------------------------- compose backward (a10)
 
 @pytest.mark.parametrize("dtype,tokens,d_out", [("f32", 64, 256), ("f32", 130, 100), ("bf16", 77, 200),
-                                               ("bf16", 300, 2056), ("bf16", 1030, 4096)])
+                                               ("bf16", 300, 2056), ("bf16", 1030, 4096), ("f16", 77, 200),
+                                               ("f16", 1030, 4096)])
 def test_compose_backward(dtype, tokens, d_out):
     rng = np.random.default_rng(tokens * 3 + d_out)
     dy_s = I.quantise(rng.standard_normal((tokens, d_out)), dtype)
@@ -283,7 +319,7 @@ def test_compose_backward(dtype, tokens, d_out):
     g32 = (1 + 0.0015 * rng.standard_normal(d_out)).astype(np.float32)
     c32 = (np.abs(rng.standard_normal(d_out)) + 0.5).astype(np.float32)
     desc = D.make_desc(d_out, 8, 8, tokens, G.dtype_code(dtype), 1.5)
-    eps = 1e-6 if dtype == "bf16" else 1e-12
+    eps = 1e-12 if dtype == "f32" else 1e-6
     dz, dm = G.empty((tokens, d_out), dtype), G.empty_f32(d_out)
     ws = G.workspace(desc, D.PHASE_COMPOSE_BACKWARD)
     D.dora_compose_backward(desc, G.to_dev(dy_s), G.to_dev(inner_s), G.to_dev(g32), G.to_dev(c32), dz, dm, ws)
@@ -375,7 +411,7 @@ def test_forward_backward_at_degenerate_sizes(cfg):
     G.assert_norm_close(G.to_f64(out["c"]), f["c"], G.TOL[cfg.dtype]["norm"])
     for k in ("y", "inner", "h"):
         G.assert_close(k, G.to_f64(out[k]), f[k], tol)
-    if cfg.dtype == "bf16":
+    if cfg.dtype != "f32":
         fused = mod.forward(fused=True)
         G.assert_close("y [fused]", G.to_f64(fused["y"]), f["y"], tol)
     b = O.backward(mod.f64("dy"), **oi)
@@ -431,7 +467,7 @@ def test_probes_run_and_copy_is_exact():
     assert float(sink.abs().max()) == 0.0
 
 
-BF16_CASES = [c for c in SMALL if c.dtype == "bf16"]
+BF16_CASES = [c for c in SMALL if c.dtype != "f32"]   # the 16-bit storage types
 
 
 @pytest.mark.parametrize("cfg", BF16_CASES, ids=[c.name for c in BF16_CASES])
@@ -439,9 +475,9 @@ def test_fused_forward_matches_oracle_and_contract_path(cfg):
     # K-concatenated forward with the compose folded into the MFMA epilogue
     mod = G.Module(cfg)
     f = O.forward(**oracle_inputs(mod))
-    tol = G.TOL["bf16"]["tensor"]
+    tol = G.TOL[cfg.dtype]["tensor"]
     out = mod.forward(fused=True)
-    G.assert_norm_close(G.to_f64(out["c"]), f["c"], G.TOL["bf16"]["norm"])
+    G.assert_norm_close(G.to_f64(out["c"]), f["c"], G.TOL[cfg.dtype]["norm"])
     G.assert_close("y", G.to_f64(out["y"]), f["y"], tol)
     G.assert_close("inner", G.to_f64(out["inner"]), f["inner"], tol)
     G.assert_close("h", G.to_f64(out["h"]), f["h"], tol)
@@ -469,19 +505,16 @@ def test_fused_forward_rejects_fp32():
 
 # ----------------------------------------------------------------------------- bias of the base layer
 
-@pytest.mark.parametrize("cfg", [SMALL[0], SMALL[2], SMALL[5], SMALL[6]], ids=[IDS[0], IDS[2], IDS[5], IDS[6]])
+@pytest.mark.parametrize("cfg", [SMALL[0], SMALL[2], SMALL[5], SMALL[6], SMALL[8]], ids=[IDS[0], IDS[2], IDS[5], IDS[6], IDS[8]])
 @pytest.mark.parametrize("fused", [False, True], ids=["compose_pass", "fused_epilogue"])
 def test_forward_with_bias(cfg, fused):
     # App. A item 2: the frozen layer's bias is not part of the compose; y = base + delta + bias
-    if fused and cfg.dtype != "bf16":
-        pytest.skip("the K-concatenated forward is bf16 only")
+    if fused and cfg.dtype == "f32":
+        pytest.skip("the K-concatenated forward is for 16-bit storage only")
     mod = G.Module(cfg)
     rng = np.random.default_rng(4242)
     bias64 = rng.normal(size=cfg.d_out)
-    if cfg.dtype == "bf16":
-        stored = I.f32_to_bf16_bits(bias64.astype(np.float32))
-    else:
-        stored = bias64.astype(np.float32)
+    stored = I.quantise(bias64, cfg.dtype)
     bias_dev = G.to_dev(stored)
     ref = O.forward(**oracle_inputs(mod), bias=I.to_f64(stored))
     out = mod.forward(fused=fused, bias=bias_dev)
