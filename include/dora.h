@@ -62,7 +62,9 @@ typedef enum {
     DORA_PHASE_FORWARD = 1,           /* dora_forward with w_norm == NULL and saved_inner == NULL (worst case) */
     DORA_PHASE_BACKWARD = 2,          /* dora_backward with saved_h / saved_inner given */
     DORA_PHASE_BACKWARD_RECOMPUTE = 3,/* dora_backward with saved_* == NULL (recomputes h and inner) */
-    DORA_PHASE_COMPOSE_BACKWARD = 4   /* dora_compose_backward */
+    DORA_PHASE_COMPOSE_BACKWARD = 4,  /* dora_compose_backward */
+    DORA_PHASE_FORWARD_DROPOUT = 5,   /* dora_forward_dropout, worst case as for DORA_PHASE_FORWARD */
+    DORA_PHASE_BACKWARD_DROPOUT = 6   /* dora_backward_dropout with everything recomputed (worst case) */
 } dora_phase;
 
 /* Scratch bytes an entry point needs for this shape.  Returns 0 for an invalid desc. */
@@ -218,6 +220,30 @@ dora_status dora_backward(const dora_desc* desc, const void* dy, const void* x, 
                           const void* saved_h, const void* saved_inner,
                           void* dx, float* dA, float* dB, float* dm,
                           void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * The module under LoRA dropout (App. B "Chunked dropout path"): the adapter branch sees its own input
+ * x_lora = dropout(x), formed by the caller (device, const, `dtype` [tokens, d_in]; the library draws no
+ * random numbers), while the frozen layer's output stays that of x.  The compose then runs on the adapter
+ * branch's own base:
+ *   y = x W^T + delta,   delta = (g-1) (.) (x_lora W^T) + g (.) (s * (x_lora A^T) B^T)  [+ bias]
+ * i.e. delta = x_lora (W' - W)^T with W' the adapted weight of Eq. 1; h and inner are those of x_lora.
+ * (The paper bounds the memory of the second base by walking d_out in slices; here it is one
+ * [tokens, d_out] scratch tensor inside the workspace, DORA_PHASE_FORWARD_DROPOUT.)
+ * Backward, norm constant:  dx = dy W (frozen path),  dx_lora = ((g-1) (.) dy) W + dh A,  dh = s (g (.) dy) B,
+ * dA = dh^T x_lora,  dB = s (g (.) dy)^T h,  dm = (sum_t dy * inner) / max(w_norm, eps); the caller applies
+ * its dropout mask to dx_lora and adds it to dx.  dx, dx_lora, dA, dB, dm may each be NULL.  saved_h /
+ * saved_inner as written by dora_forward_dropout, or NULL (recomputed from x_lora).  With x_lora == x the
+ * results are those of dora_forward / dora_backward (dx + dx_lora = dx of the plain module).
+ */
+dora_status dora_forward_dropout(const dora_desc* desc, const void* x, const void* x_lora, const void* W,
+                                 const void* A, const void* B, const float* m, const float* w_norm,
+                                 const void* bias, void* y, void* saved_h, void* saved_inner, float* w_norm_out,
+                                 void* ws, size_t ws_bytes, void* stream);
+dora_status dora_backward_dropout(const dora_desc* desc, const void* dy, const void* x_lora, const void* W,
+                                  const void* A, const void* B, const float* m, const float* w_norm,
+                                  const void* saved_h, const void* saved_inner, void* dx, void* dx_lora,
+                                  float* dA, float* dB, float* dm, void* ws, size_t ws_bytes, void* stream);
 
 const char* dora_status_str(int status);
 

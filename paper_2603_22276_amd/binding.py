@@ -15,12 +15,12 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libdora.so")
 
 DORA_F32, DORA_BF16, DORA_F16 = 0, 1, 2
-PHASE_NORM, PHASE_FORWARD, PHASE_BACKWARD, PHASE_BACKWARD_RECOMPUTE, PHASE_COMPOSE_BACKWARD = range(5)
+PHASE_NORM, PHASE_FORWARD, PHASE_BACKWARD, PHASE_BACKWARD_RECOMPUTE, PHASE_COMPOSE_BACKWARD, PHASE_FORWARD_DROPOUT, PHASE_BACKWARD_DROPOUT = range(7)
 K_COUNT = 19
 
 EXPORTS = (
     "dora_workspace_bytes", "dora_norm", "dora_norm_static", "dora_norm_static_max_bytes", "dora_base_sq", "dora_norm_cached", "dora_norm_terms", "dora_norm_assemble", "dora_mag_scale", "dora_compose", "dora_compose_backward",
-    "dora_project", "dora_forward", "dora_forward_fused", "dora_backward", "dora_status_str",
+    "dora_project", "dora_forward", "dora_forward_fused", "dora_backward", "dora_forward_dropout", "dora_backward_dropout", "dora_status_str",
     "dora_probe_copy", "dora_probe_mfma",
     "dora_trace_enable", "dora_trace_select", "dora_trace_reset", "dora_trace_collect", "dora_trace_get", "dora_trace_name",
 )
@@ -68,10 +68,12 @@ def lib() -> ctypes.CDLL:
         L.dora_forward.argtypes = [dp, vp, vp, vp, vp, fp, fp, vp, vp, vp, vp, fp, vp, sz, vp]
         L.dora_forward_fused.argtypes = L.dora_forward.argtypes
         L.dora_backward.argtypes = [dp, vp, vp, vp, vp, vp, fp, fp, vp, vp, vp, fp, fp, fp, vp, sz, vp]
+        L.dora_forward_dropout.argtypes = [dp, vp, vp, vp, vp, vp, fp, fp, vp, vp, vp, vp, fp, vp, sz, vp]
+        L.dora_backward_dropout.argtypes = [dp, vp, vp, vp, vp, vp, fp, fp, vp, vp, vp, vp, fp, fp, fp, vp, sz, vp]
         L.dora_probe_copy.argtypes = [vp, vp, sz, vp]
         L.dora_probe_mfma.argtypes = [fp, ctypes.c_int, ctypes.c_int, vp]
         for f in (L.dora_probe_copy, L.dora_probe_mfma, L.dora_norm, L.dora_norm_static, L.dora_base_sq, L.dora_norm_cached, L.dora_norm_terms, L.dora_norm_assemble, L.dora_mag_scale, L.dora_compose, L.dora_compose_backward, L.dora_project, L.dora_forward, L.dora_forward_fused,
-                  L.dora_backward, L.dora_trace_collect, L.dora_trace_get):
+                  L.dora_backward, L.dora_forward_dropout, L.dora_backward_dropout, L.dora_trace_collect, L.dora_trace_get):
             f.restype = ctypes.c_int
         L.dora_status_str.argtypes = [ctypes.c_int]
         L.dora_status_str.restype = ctypes.c_char_p
@@ -197,6 +199,19 @@ def dora_backward(desc, dy, x, W, A, B, m, w_norm, saved_h, saved_inner, dx, dA,
     _check(lib().dora_backward(ctypes.byref(desc), _p(dy), _p(x), _p(W), _p(A), _p(B), _p(m), _p(w_norm), _p(saved_h),
                                _p(saved_inner), _p(dx), _p(dA), _p(dB), _p(dm), _p(ws), _nbytes(ws), _stream(stream)),
            "dora_backward")
+
+
+def dora_forward_dropout(desc, x, x_lora, W, A, B, m, w_norm, bias, y, saved_h, saved_inner, w_norm_out, ws, stream=None) -> None:
+    _check(lib().dora_forward_dropout(ctypes.byref(desc), _p(x), _p(x_lora), _p(W), _p(A), _p(B), _p(m), _p(w_norm), _p(bias),
+                                      _p(y), _p(saved_h), _p(saved_inner), _p(w_norm_out), _p(ws), _nbytes(ws),
+                                      _stream(stream)), "dora_forward_dropout")
+
+
+def dora_backward_dropout(desc, dy, x_lora, W, A, B, m, w_norm, saved_h, saved_inner, dx, dx_lora, dA, dB, dm, ws,
+                          stream=None) -> None:
+    _check(lib().dora_backward_dropout(ctypes.byref(desc), _p(dy), _p(x_lora), _p(W), _p(A), _p(B), _p(m), _p(w_norm),
+                                       _p(saved_h), _p(saved_inner), _p(dx), _p(dx_lora), _p(dA), _p(dB), _p(dm), _p(ws),
+                                       _nbytes(ws), _stream(stream)), "dora_backward_dropout")
 
 
 def dora_probe_copy(src, dst, nbytes: int, stream=None) -> None:

@@ -159,12 +159,15 @@ hipError_t launch_sgemm_f32(const SgemmArgs& a, int trace_id, hipStream_t stream
 
 // ---- element-wise / reduction kernels -----------------------------------------------------------
 hipError_t launch_mag_scale(const float* m, const float* c, float eps, float* g, float* gm1, int d_out, hipStream_t st);
+// write_delta: 0 out = base + delta (+ bias), 1 out = delta, 2 out += delta (+ bias)
 hipError_t launch_compose_fwd(int dtype, const void* base, const void* lora, const float* g, const float* gm1,
                               const void* bias, float s, void* out, int write_delta, void* inner, int64_t tokens,
                               int d_out, hipStream_t st);
 int compose_bwd_slabs(int64_t tokens, int d_out, int dtype);
-hipError_t launch_compose_bwd(int dtype, const void* dy, const void* inner, const float* g, void* dz,
-                              float* partial /* [slabs][d_out] or nullptr */, int64_t tokens, int d_out, hipStream_t st);
+// dzb != nullptr: also dzb = gm1 (.) dy (then gm1 must be given)
+hipError_t launch_compose_bwd(int dtype, const void* dy, const void* inner, const float* g, const float* gm1, void* dz,
+                              void* dzb, float* partial /* [slabs][d_out] or nullptr */, int64_t tokens, int d_out,
+                              hipStream_t st);
 hipError_t launch_dm_final(const float* partial, int slabs, const float* c, float eps, float* dm, int d_out, hipStream_t st);
 // G = sum of partials; Ghi + Glo ~ G as two 16-bit terms of element type dt (both may be nullptr)
 hipError_t launch_gram_reduce(const float* partials, int ksplit, int r, float* G, bf16_t* Ghi, bf16_t* Glo, int dt,

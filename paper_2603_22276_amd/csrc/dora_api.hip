@@ -295,10 +295,10 @@ dora_status norm_impl(const dora_desc* d, const void* W, const void* A, const vo
 struct FwdPlan {
     NormPlan norm;
     float *c, *g, *gm1;
-    void *h, *lora, *hs;
+    void *h, *lora, *hs, *base_a;
 };
 void plan_fwd(const dora_desc* d, Bump& b, FwdPlan& p, bool need_norm, bool need_h, bool need_lora,
-              bool need_hs = false)
+              bool need_hs = false, bool need_base_a = false)
 {
     memset(&p, 0, sizeof(p));
     if (need_norm) plan_norm(d, b, p.norm);
@@ -308,14 +308,16 @@ void plan_fwd(const dora_desc* d, Bump& b, FwdPlan& p, bool need_norm, bool need
     if (need_h) p.h = b.take_bytes((size_t)d->tokens * d->r * esize(d->dtype));
     if (need_lora) p.lora = b.take_bytes((size_t)d->tokens * d->d_out * esize(d->dtype));
     if (need_hs) p.hs = b.take_bytes((size_t)d->tokens * d->r * esize(d->dtype));
+    if (need_base_a) p.base_a = b.take_bytes((size_t)d->tokens * d->d_out * esize(d->dtype));
 }
 
 struct BwdPlan {
     NormPlan norm;
     float *c, *g, *gm1, *dm_partial;
-    void *dz, *dh, *h, *inner;
+    void *dz, *dh, *h, *inner, *dzb;
 };
-void plan_bwd(const dora_desc* d, Bump& b, BwdPlan& p, bool need_norm, bool need_h, bool need_inner)
+void plan_bwd(const dora_desc* d, Bump& b, BwdPlan& p, bool need_norm, bool need_h, bool need_inner,
+              bool need_dzb = false)
 {
     memset(&p, 0, sizeof(p));
     if (need_norm) plan_norm(d, b, p.norm);
@@ -327,6 +329,7 @@ void plan_bwd(const dora_desc* d, Bump& b, BwdPlan& p, bool need_norm, bool need
     p.dh = b.take_bytes((size_t)d->tokens * d->r * esize(d->dtype));
     if (need_h) p.h = b.take_bytes((size_t)d->tokens * d->r * esize(d->dtype));
     if (need_inner) p.inner = b.take_bytes((size_t)d->tokens * d->d_out * esize(d->dtype));
+    if (need_dzb) p.dzb = b.take_bytes((size_t)d->tokens * d->d_out * esize(d->dtype));
 }
 
 dora_status check_ws(void* ws, size_t ws_bytes, size_t need)
@@ -339,12 +342,13 @@ dora_status check_ws(void* ws, size_t ws_bytes, size_t need)
 }
 
 // base = x W^T, h = x A^T, lora = h B^T (App. A item 1)
+// xa: the adapter branch's input (x itself unless LoRA dropout gives that branch an input of its own)
 dora_status forward_contractions(const dora_desc* d, const void* x, const void* W, const void* A, const void* B,
-                                 void* base, void* h, void* lora, hipStream_t st)
+                                 void* base, void* h, void* lora, hipStream_t st, const void* xa = nullptr)
 {
     const int T = (int)d->tokens, d_out = (int)d->d_out, d_in = (int)d->d_in, r = (int)d->r;
     Seg s0{x, d_in, W, d_in, d_in};
-    Seg s1{x, d_in, A, d_in, d_in};
+    Seg s1{xa ? xa : x, d_in, A, d_in, d_in};
     // (base and h are NOT paired into one launch: h's extra tiles would form a fifth, nearly empty
     // round behind the four full rounds of 256 x 256 base tiles and cost more than a launch of their own)
     DORA_HIP(contract(d->dtype, true, true, T, d_out, &s0, 1, 1.f, base, d_out, false, DORA_K_GEMM_BASE, st));
@@ -389,6 +393,8 @@ size_t dora_workspace_bytes(const dora_desc* desc, int phase)
         case DORA_PHASE_FORWARD: { FwdPlan p; plan_fwd(desc, b, p, true, true, true, true); break; }
         case DORA_PHASE_BACKWARD: { BwdPlan p; plan_bwd(desc, b, p, false, false, false); break; }
         case DORA_PHASE_BACKWARD_RECOMPUTE: { BwdPlan p; plan_bwd(desc, b, p, true, true, true); break; }
+        case DORA_PHASE_FORWARD_DROPOUT: { FwdPlan p; plan_fwd(desc, b, p, true, true, true, false, true); break; }
+        case DORA_PHASE_BACKWARD_DROPOUT: { BwdPlan p; plan_bwd(desc, b, p, true, true, true, true); break; }
         default: return 0;
     }
     return b.off > 0 ? b.off : 256;
@@ -506,7 +512,7 @@ dora_status dora_compose(const dora_desc* desc, const void* base, const void* lo
     if (st != DORA_OK) return st;
     DORA_REQ_PTR(base); DORA_REQ_PTR(lora); DORA_REQ_PTR(g); DORA_REQ_PTR(out);
     DORA_OPT_PTR(gm1); DORA_OPT_PTR(inner);
-    DORA_HIP(launch_compose_fwd(desc->dtype, base, lora, g, gm1, nullptr, desc->s, out, write_delta, inner, desc->tokens,
+    DORA_HIP(launch_compose_fwd(desc->dtype, base, lora, g, gm1, nullptr, desc->s, out, write_delta ? 1 : 0, inner, desc->tokens,
                                 (int)desc->d_out, (hipStream_t)stream));
     return DORA_OK;
 }
@@ -526,7 +532,7 @@ dora_status dora_compose_backward(const dora_desc* desc, const void* dy, const v
         partial = (float*)ws;
     }
     hipStream_t s = (hipStream_t)stream;
-    DORA_HIP(launch_compose_bwd(desc->dtype, dy, inner, g, dz, partial, desc->tokens, (int)desc->d_out, s));
+    DORA_HIP(launch_compose_bwd(desc->dtype, dy, inner, g, nullptr, dz, nullptr, partial, desc->tokens, (int)desc->d_out, s));
     if (dm)
         DORA_HIP(launch_dm_final(partial, compose_bwd_slabs(desc->tokens, (int)desc->d_out, desc->dtype), w_norm, eff_eps(desc), dm, (int)desc->d_out, s));
     return DORA_OK;
@@ -543,24 +549,26 @@ dora_status dora_project(const dora_desc* desc, const void* x, const void* W, co
     return forward_contractions(desc, x, W, A, B, base, h, lora, (hipStream_t)stream);
 }
 
-dora_status dora_forward(const dora_desc* desc, const void* x, const void* W, const void* A, const void* B,
-                         const float* m, const float* w_norm, const void* bias, void* y, void* saved_h, void* saved_inner,
-                         float* w_norm_out, void* ws, size_t ws_bytes, void* stream)
+static dora_status forward_impl(const dora_desc* desc, const void* x, const void* x_lora, const void* W, const void* A,
+                                const void* B, const float* m, const float* w_norm, const void* bias, void* y, void* saved_h,
+                                void* saved_inner, float* w_norm_out, void* ws, size_t ws_bytes, void* stream)
 {
     dora_status st = check_desc(desc, true);
     if (st != DORA_OK) return st;
     DORA_REQ_PTR(W); DORA_REQ_PTR(A); DORA_REQ_PTR(B); DORA_REQ_PTR(m);
     if (desc->tokens > 0) { DORA_REQ_PTR(x); DORA_REQ_PTR(y); }
+    DORA_OPT_PTR(x_lora);
     DORA_OPT_PTR(w_norm); DORA_OPT_PTR(bias); DORA_OPT_PTR(saved_h); DORA_OPT_PTR(saved_inner); DORA_OPT_PTR(w_norm_out);
     const bool need_norm = (w_norm == nullptr);
+    const bool dropout = (x_lora != nullptr);
     Bump sizing(nullptr);
     FwdPlan p;
-    plan_fwd(desc, sizing, p, need_norm, saved_h == nullptr, saved_inner == nullptr);
+    plan_fwd(desc, sizing, p, need_norm, saved_h == nullptr, saved_inner == nullptr, false, dropout);
     if ((st = check_ws(ws, ws_bytes, sizing.off)) != DORA_OK) return st;
     Bump b(ws);
-    plan_fwd(desc, b, p, need_norm, saved_h == nullptr, saved_inner == nullptr);
+    plan_fwd(desc, b, p, need_norm, saved_h == nullptr, saved_inner == nullptr, false, dropout);
     hipStream_t s = (hipStream_t)stream;
-    const int d_out = (int)desc->d_out;
+    const int T = (int)desc->tokens, d_out = (int)desc->d_out, d_in = (int)desc->d_in;
 
     const float* c = w_norm;
     if (need_norm) {
@@ -570,15 +578,38 @@ dora_status dora_forward(const dora_desc* desc, const void* x, const void* W, co
     } else if (w_norm_out && w_norm_out != w_norm) {
         DORA_HIP(hipMemcpyAsync(w_norm_out, w_norm, sizeof(float) * d_out, hipMemcpyDeviceToDevice, s));
     }
-    if (desc->tokens == 0) return DORA_OK;
+    if (T == 0) return DORA_OK;
     DORA_HIP(launch_mag_scale(m, c, eff_eps(desc), p.g, p.gm1, d_out, s));
     // base lands in y and lora in the inner buffer; the compose pass then runs in place on both
     void* h = saved_h ? saved_h : p.h;
     void* lora = saved_inner ? saved_inner : p.lora;
-    if ((st = forward_contractions(desc, x, W, A, B, y, h, lora, s)) != DORA_OK) return st;
-    DORA_HIP(launch_compose_fwd(desc->dtype, y, lora, p.g, p.gm1, bias, desc->s, y, 0, saved_inner, desc->tokens, d_out,
-                                s));
+    if ((st = forward_contractions(desc, x, W, A, B, y, h, lora, s, x_lora)) != DORA_OK) return st;
+    if (!dropout) {
+        DORA_HIP(launch_compose_fwd(desc->dtype, y, lora, p.g, p.gm1, bias, desc->s, y, 0, saved_inner, T, d_out, s));
+        return DORA_OK;
+    }
+    // LoRA dropout: the compose runs on the adapter branch's own base x_lora W^T and its delta is added to
+    // the frozen layer's output already in y
+    Seg sa{x_lora, d_in, W, d_in, d_in};
+    DORA_HIP(contract(desc->dtype, true, true, T, d_out, &sa, 1, 1.f, p.base_a, d_out, false, DORA_K_GEMM_BASE, s));
+    DORA_HIP(launch_compose_fwd(desc->dtype, p.base_a, lora, p.g, p.gm1, bias, desc->s, y, 2, saved_inner, T, d_out, s));
     return DORA_OK;
+}
+
+dora_status dora_forward(const dora_desc* desc, const void* x, const void* W, const void* A, const void* B,
+                         const float* m, const float* w_norm, const void* bias, void* y, void* saved_h, void* saved_inner,
+                         float* w_norm_out, void* ws, size_t ws_bytes, void* stream)
+{
+    return forward_impl(desc, x, nullptr, W, A, B, m, w_norm, bias, y, saved_h, saved_inner, w_norm_out, ws, ws_bytes, stream);
+}
+
+dora_status dora_forward_dropout(const dora_desc* desc, const void* x, const void* x_lora, const void* W, const void* A,
+                                 const void* B, const float* m, const float* w_norm, const void* bias, void* y,
+                                 void* saved_h, void* saved_inner, float* w_norm_out, void* ws, size_t ws_bytes,
+                                 void* stream)
+{
+    if (desc && desc->tokens > 0 && !x_lora) return DORA_ERR_NULL;
+    return forward_impl(desc, x, x_lora, W, A, B, m, w_norm, bias, y, saved_h, saved_inner, w_norm_out, ws, ws_bytes, stream);
 }
 
 dora_status dora_forward_fused(const dora_desc* desc, const void* x, const void* W, const void* A, const void* B,
@@ -629,26 +660,32 @@ dora_status dora_forward_fused(const dora_desc* desc, const void* x, const void*
     return DORA_OK;
 }
 
-dora_status dora_backward(const dora_desc* desc, const void* dy, const void* x, const void* W, const void* A,
-                          const void* B, const float* m, const float* w_norm, const void* saved_h,
-                          const void* saved_inner, void* dx, float* dA, float* dB, float* dm, void* ws,
-                          size_t ws_bytes, void* stream)
+// x_lora == nullptr: the plain module (dx = dz W + dh A).  Otherwise the adapter branch has its own input:
+// dx = dy W (frozen path; x itself is not needed), dx_lora = ((g-1) dy) W + dh A, dA and the recomputed
+// h / inner come from x_lora.
+static dora_status backward_impl(const dora_desc* desc, const void* dy, const void* x, const void* x_lora, const void* W,
+                                 const void* A, const void* B, const float* m, const float* w_norm, const void* saved_h,
+                                 const void* saved_inner, void* dx, void* dx_lora, float* dA, float* dB, float* dm,
+                                 void* ws, size_t ws_bytes, void* stream)
 {
     dora_status st = check_desc(desc, true);
     if (st != DORA_OK) return st;
+    const bool dropout = (x_lora != nullptr);
+    const void* xa = dropout ? x_lora : x;
     DORA_REQ_PTR(W); DORA_REQ_PTR(A); DORA_REQ_PTR(B); DORA_REQ_PTR(m);
-    if (desc->tokens > 0) { DORA_REQ_PTR(dy); DORA_REQ_PTR(x); }
+    if (desc->tokens > 0) { DORA_REQ_PTR(dy); DORA_REQ_PTR(xa); }
     DORA_OPT_PTR(w_norm); DORA_OPT_PTR(saved_h); DORA_OPT_PTR(saved_inner);
-    DORA_OPT_PTR(dx); DORA_OPT_PTR(dA); DORA_OPT_PTR(dB); DORA_OPT_PTR(dm);
+    DORA_OPT_PTR(dx); DORA_OPT_PTR(dx_lora); DORA_OPT_PTR(dA); DORA_OPT_PTR(dB); DORA_OPT_PTR(dm);
     const bool need_norm = (w_norm == nullptr);
     const bool need_inner = (dm != nullptr) && (saved_inner == nullptr);
     const bool need_h = (saved_h == nullptr) && (dB != nullptr || need_inner);
+    const bool need_dzb = dropout && (dx_lora != nullptr);
     Bump sizing(nullptr);
     BwdPlan p;
-    plan_bwd(desc, sizing, p, need_norm, need_h, need_inner);
+    plan_bwd(desc, sizing, p, need_norm, need_h, need_inner, need_dzb);
     if ((st = check_ws(ws, ws_bytes, sizing.off)) != DORA_OK) return st;
     Bump b(ws);
-    plan_bwd(desc, b, p, need_norm, need_h, need_inner);
+    plan_bwd(desc, b, p, need_norm, need_h, need_inner, need_dzb);
     hipStream_t s = (hipStream_t)stream;
     const int T = (int)desc->tokens, d_out = (int)desc->d_out, d_in = (int)desc->d_in, r = (int)desc->r;
     const int dt = desc->dtype;
@@ -667,36 +704,49 @@ dora_status dora_backward(const dora_desc* desc, const void* dy, const void* x, 
         // then inner = s*lora + base in place; the dz buffer is overwritten by dz afterwards
         void* hbuf = saved_h ? nullptr : p.h;
         if (saved_h) {
-            Seg s0{x, d_in, W, d_in, d_in};
+            Seg s0{xa, d_in, W, d_in, d_in};
             DORA_HIP(contract(dt, true, true, T, d_out, &s0, 1, 1.f, p.dz, d_out, false, DORA_K_GEMM_BASE, s));
             Seg s2{saved_h, r, B, r, r};
             DORA_HIP(contract(dt, true, true, T, d_out, &s2, 1, 1.f, p.inner, d_out, false, DORA_K_GEMM_LORA, s));
         } else {
-            if ((st = forward_contractions(desc, x, W, A, B, p.dz, hbuf, p.inner, s)) != DORA_OK) return st;
+            if ((st = forward_contractions(desc, xa, W, A, B, p.dz, hbuf, p.inner, s)) != DORA_OK) return st;
             h = hbuf;
         }
         DORA_HIP(launch_compose_fwd(dt, p.dz, p.inner, p.g, p.gm1, nullptr, desc->s, nullptr, 0, p.inner, T, d_out, s));
         inner = p.inner;
     } else if (T > 0 && need_h) {
-        Seg s1{x, d_in, A, d_in, d_in};
+        Seg s1{xa, d_in, A, d_in, d_in};
         DORA_HIP(contract(dt, true, true, T, r, &s1, 1, 1.f, p.h, r, false, DORA_K_GEMM_H, s));
         h = p.h;
     }
 
-    // compose backward: dz = g*dy and the fused two-stage column reduction for dm
-    DORA_HIP(launch_compose_bwd(dt, dy, inner, p.g, p.dz, dm ? p.dm_partial : nullptr, T, d_out, s));
+    // compose backward: dz = g*dy (and (g-1)*dy for a separate adapter input) and the fused two-stage column
+    // reduction for dm
+    DORA_HIP(launch_compose_bwd(dt, dy, inner, p.g, p.gm1, p.dz, need_dzb ? p.dzb : nullptr, dm ? p.dm_partial : nullptr, T,
+                                d_out, s));
     if (dm) DORA_HIP(launch_dm_final(p.dm_partial, compose_bwd_slabs(T, d_out, dt), c, eff_eps(desc), dm, d_out, s));
 
-    // dh = s * dz B   (gradient reaching h = x A^T)
-    if (dx || dA) {
+    // dh = s * dz B   (gradient reaching h)
+    if ((dropout ? dx_lora : dx) || dA) {
         Seg sh{p.dz, d_out, B, r, d_out};
         DORA_HIP(contract(dt, true, false, T, r, &sh, 1, desc->s, p.dh, r, false, DORA_K_GEMM_DH, s));
     }
-    if (dx) {  // dx = dz W + dh A : one contraction over the concatenated K range
-        Seg sx[2] = {{p.dz, d_out, W, d_in, d_out}, {p.dh, r, A, d_in, r}};
-        DORA_HIP(contract(dt, true, false, T, d_in, sx, 2, 1.f, dx, d_in, false, DORA_K_GEMM_DX, s));
+    if (!dropout) {
+        if (dx) {  // dx = dz W + dh A : one contraction over the concatenated K range
+            Seg sx[2] = {{p.dz, d_out, W, d_in, d_out}, {p.dh, r, A, d_in, r}};
+            DORA_HIP(contract(dt, true, false, T, d_in, sx, 2, 1.f, dx, d_in, false, DORA_K_GEMM_DX, s));
+        }
+    } else {
+        if (dx) {  // frozen path: dx = dy W
+            Seg sx{dy, d_out, W, d_in, d_out};
+            DORA_HIP(contract(dt, true, false, T, d_in, &sx, 1, 1.f, dx, d_in, false, DORA_K_GEMM_DX, s));
+        }
+        if (dx_lora) {  // adapter path: dx_lora = ((g-1) dy) W + dh A
+            Seg sx[2] = {{p.dzb, d_out, W, d_in, d_out}, {p.dh, r, A, d_in, r}};
+            DORA_HIP(contract(dt, true, false, T, d_in, sx, 2, 1.f, dx_lora, d_in, false, DORA_K_GEMM_DX, s));
+        }
     }
-    Seg sa{p.dh, r, x, d_in, T};   // dA = dh^T x
+    Seg sa{p.dh, r, xa, d_in, T};  // dA = dh^T xa
     Seg sb{p.dz, d_out, h, r, T};  // dB = s * dz^T h
     if (dA && dB && is16(dt)) {
         // the two weight gradients are independent and individually too small to fill the chip: one launch
@@ -708,6 +758,26 @@ dora_status dora_backward(const dora_desc* desc, const void* dy, const void* x, 
         if (dB) DORA_HIP(contract(dt, false, false, d_out, r, &sb, 1, desc->s, dB, r, true, DORA_K_GEMM_DB, s));
     }
     return DORA_OK;
+}
+
+dora_status dora_backward(const dora_desc* desc, const void* dy, const void* x, const void* W, const void* A,
+                          const void* B, const float* m, const float* w_norm, const void* saved_h,
+                          const void* saved_inner, void* dx, float* dA, float* dB, float* dm, void* ws,
+                          size_t ws_bytes, void* stream)
+{
+    return backward_impl(desc, dy, x, nullptr, W, A, B, m, w_norm, saved_h, saved_inner, dx, nullptr, dA, dB, dm, ws, ws_bytes,
+                         stream);
+}
+
+dora_status dora_backward_dropout(const dora_desc* desc, const void* dy, const void* x_lora, const void* W, const void* A,
+                                  const void* B, const float* m, const float* w_norm, const void* saved_h,
+                                  const void* saved_inner, void* dx, void* dx_lora, float* dA, float* dB, float* dm,
+                                  void* ws, size_t ws_bytes, void* stream)
+{
+    if (desc && desc->tokens > 0 && !x_lora) return DORA_ERR_NULL;
+    if (desc && desc->tokens == 0 && !x_lora) x_lora = W;  // nothing of it is read; keeps the dropout code path
+    return backward_impl(desc, dy, nullptr, x_lora, W, A, B, m, w_norm, saved_h, saved_inner, dx, dx_lora, dA, dB, dm, ws,
+                         ws_bytes, stream);
 }
 
 dora_status dora_probe_copy(const void* src, void* dst, size_t bytes, void* stream)

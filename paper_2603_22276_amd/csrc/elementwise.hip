@@ -184,7 +184,9 @@ __global__ void rownorm_s0_16_kernel(const T* __restrict__ W, float* __restrict_
 
 // ------------------------------------------------------------------------------------------------
 // Compose forward.  delta = gm1*base + g*(s*lora);  out = delta or base + delta;  inner = s*lora + base.
-// OUTMODE: 0 = no out tensor (inner only), 1 = out = base + delta, 2 = out = delta.
+// OUTMODE: 0 = no out tensor (inner only), 1 = out = base + delta, 2 = out = delta, 3 = out += delta (the
+// frozen layer's output is already in out and base is the adapter branch's own base, App. B "Chunked
+// dropout path").
 template <typename T, int OUTMODE, bool INNER>
 __global__ __launch_bounds__(CW* CH) void compose_fwd_kernel(const T* base_, const T* lora_,  // out may alias base, inner may alias lora
                                                              
@@ -205,33 +207,35 @@ __global__ __launch_bounds__(CW* CH) void compose_fwd_kernel(const T* base_, con
         g1[i] = gm1 ? gm1[col + i] : gv[i] - 1.0f;
         bv[i] = 0.f;
     }
-    if (OUTMODE == 1 && bias) V::unpack(*reinterpret_cast<const raw_t*>(bias + col), bv);
+    if ((OUTMODE == 1 || OUTMODE == 3) && bias) V::unpack(*reinterpret_cast<const raw_t*>(bias + col), bv);
     const int64_t row_begin = (int64_t)blockIdx.y * rows_per_wg;
     int64_t row_end = row_begin + rows_per_wg;
     if (row_end > tokens) row_end = tokens;
     constexpr int UNROLL = 4;
     for (int64_t row = row_begin + threadIdx.y; row < row_end; row += CH * UNROLL) {
-        raw_t b[UNROLL], l[UNROLL];
+        raw_t b[UNROLL], l[UNROLL], y0[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             int64_t rr = row + u * CH;
             if (rr < row_end) {
                 b[u] = *reinterpret_cast<const raw_t*>(base_ + rr * d_out + col);
                 l[u] = *reinterpret_cast<const raw_t*>(lora_ + rr * d_out + col);
+                if (OUTMODE == 3) y0[u] = *reinterpret_cast<const raw_t*>(out_ + rr * d_out + col);
             }
         }
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             int64_t rr = row + u * CH;
             if (rr < row_end) {
-                float bf[N], lf[N], of[N], inf[N];
+                float bf[N], lf[N], of[N], inf[N], yf[N];
                 V::unpack(b[u], bf);
                 V::unpack(l[u], lf);
+                if (OUTMODE == 3) V::unpack(y0[u], yf);
 #pragma unroll
                 for (int i = 0; i < N; ++i) {
                     float sl = s * lf[i];                        // canonical order: s*lora first, then g*(.)
                     float delta = fmaf(g1[i], bf[i], gv[i] * sl);
-                    of[i] = (OUTMODE == 2) ? delta : (bf[i] + delta) + bv[i];
+                    of[i] = (OUTMODE == 2) ? delta : (((OUTMODE == 3) ? yf[i] : bf[i]) + delta) + bv[i];
                     inf[i] = sl + bf[i];
                 }
                 if (OUTMODE != 0) store_stream(out_ + rr * d_out + col, V::pack(of));
@@ -242,9 +246,12 @@ __global__ __launch_bounds__(CW* CH) void compose_fwd_kernel(const T* base_, con
 }
 
 // Compose backward: dz = g*dy, and (DM) the first stage of the column sum of dy*inner over this slab.
-template <typename T, bool DM>
+// SPLIT: also dzb = (g-1)*dy, the gradient reaching the adapter branch's own base when that branch has an
+// input of its own (dz then reaches lora only, scaled by s in the products that follow).
+template <typename T, bool DM, bool SPLIT>
 __global__ __launch_bounds__(CW* CH) void compose_bwd_kernel(const T* __restrict__ dy_, const T* __restrict__ inner_,
-                                                              const float* __restrict__ g, T* __restrict__ dz_,
+                                                              const float* __restrict__ g, const float* __restrict__ gm1,
+                                                              T* __restrict__ dz_, T* __restrict__ dzb_,
                                                               float* __restrict__ partial, int64_t tokens, int d_out,
                                                               int rows_per_wg)
 {
@@ -254,10 +261,11 @@ __global__ __launch_bounds__(CW* CH) void compose_bwd_kernel(const T* __restrict
     __shared__ float red[CH][CW * N];
     const int col = (blockIdx.x * CW + threadIdx.x) * N;
     const bool active = col < d_out;
-    float gv[N], acc[N];
+    float gv[N], g1[N], acc[N];
 #pragma unroll
     for (int i = 0; i < N; ++i) {
         gv[i] = active ? g[col + i] : 0.f;
+        g1[i] = (SPLIT && active) ? gm1[col + i] : 0.f;
         acc[i] = 0.f;
     }
     const int64_t row_begin = (int64_t)blockIdx.y * rows_per_wg;
@@ -287,15 +295,17 @@ __global__ __launch_bounds__(CW* CH) void compose_bwd_kernel(const T* __restrict
             for (int u = 0; u < UNROLL; ++u) {
                 int64_t rr = row + u * CH;
                 if (rr < row_end) {
-                    float df[N], nf[N], zf[N];
+                    float df[N], nf[N], zf[N], zb[N];
                     V::unpack(d[u], df);
                     if (DM) V::unpack(in[u], nf);
 #pragma unroll
                     for (int i = 0; i < N; ++i) {
                         zf[i] = gv[i] * df[i];
+                        if (SPLIT) zb[i] = g1[i] * df[i];
                         if (DM) acc[i] = fmaf(df[i], nf[i], acc[i]);
                     }
                     store_stream(dz_ + rr * d_out + col, V::pack(zf));
+                    if (SPLIT) store_stream(dzb_ + rr * d_out + col, V::pack(zb));
                 }
             }
 #pragma unroll
@@ -427,6 +437,7 @@ static hipError_t compose_fwd_t(const void* base, const void* lora, const float*
 #define DORA_LAUNCH_FWD(D, I) \
     compose_fwd_kernel<T, D, I><<<grid, block, 0, st>>>(b, l, g, gm1, (const T*)bias, s, o, in, tokens, d_out, FWD_ROWS_PER_WG)
     if (!out) { DORA_LAUNCH_FWD(0, true); }
+    else if (write_delta == 2) { if (inner) DORA_LAUNCH_FWD(3, true); else DORA_LAUNCH_FWD(3, false); }
     else if (write_delta) { if (inner) DORA_LAUNCH_FWD(2, true); else DORA_LAUNCH_FWD(2, false); }
     else { if (inner) DORA_LAUNCH_FWD(1, true); else DORA_LAUNCH_FWD(1, false); }
 #undef DORA_LAUNCH_FWD
@@ -455,8 +466,8 @@ int compose_bwd_slabs(int64_t tokens, int d_out, int dtype)
 }
 
 template <typename T>
-static hipError_t compose_bwd_t(const void* dy, const void* inner, const float* g, void* dz, float* partial,
-                                int64_t tokens, int d_out, hipStream_t st)
+static hipError_t compose_bwd_t(const void* dy, const void* inner, const float* g, const float* gm1, void* dz, void* dzb,
+                                float* partial, int64_t tokens, int d_out, hipStream_t st)
 {
     constexpr int N = Vec<T>::N;
     int cpr = d_out / N;
@@ -464,23 +475,23 @@ static hipError_t compose_bwd_t(const void* dy, const void* inner, const float* 
     const int BWD_ROWS_PER_WG = compose_bwd_rows(tokens, d_out, dtype);
     dim3 grid((cpr + CW - 1) / CW, (unsigned)compose_bwd_slabs(tokens, d_out, dtype));
     dim3 block(CW, CH);
-    if (partial)
-        compose_bwd_kernel<T, true><<<grid, block, 0, st>>>((const T*)dy, (const T*)inner, g, (T*)dz, partial, tokens,
-                                                             d_out, BWD_ROWS_PER_WG);
-    else
-        compose_bwd_kernel<T, false><<<grid, block, 0, st>>>((const T*)dy, nullptr, g, (T*)dz, nullptr, tokens, d_out,
-                                                              BWD_ROWS_PER_WG);
+#define DORA_LAUNCH_BWD(DM, SP)                                                                                   \
+    compose_bwd_kernel<T, DM, SP><<<grid, block, 0, st>>>((const T*)dy, (const T*)inner, g, gm1, (T*)dz, (T*)dzb, partial, \
+                                                           tokens, d_out, BWD_ROWS_PER_WG)
+    if (partial) { if (dzb) DORA_LAUNCH_BWD(true, true); else DORA_LAUNCH_BWD(true, false); }
+    else { if (dzb) DORA_LAUNCH_BWD(false, true); else DORA_LAUNCH_BWD(false, false); }
+#undef DORA_LAUNCH_BWD
     return hipGetLastError();
 }
 
-hipError_t launch_compose_bwd(int dtype, const void* dy, const void* inner, const float* g, void* dz, float* partial,
-                              int64_t tokens, int d_out, hipStream_t st)
+hipError_t launch_compose_bwd(int dtype, const void* dy, const void* inner, const float* g, const float* gm1, void* dz,
+                              void* dzb, float* partial, int64_t tokens, int d_out, hipStream_t st)
 {
     if (tokens == 0 || d_out == 0) return hipSuccess;
     TraceScope ts(DORA_K_COMPOSE_BWD, st);
-    if (dtype == DORA_BF16) return compose_bwd_t<bf16_t>(dy, inner, g, dz, partial, tokens, d_out, st);
-    if (dtype == DORA_F16) return compose_bwd_t<f16_t>(dy, inner, g, dz, partial, tokens, d_out, st);
-    return compose_bwd_t<float>(dy, inner, g, dz, partial, tokens, d_out, st);
+    if (dtype == DORA_BF16) return compose_bwd_t<bf16_t>(dy, inner, g, gm1, dz, dzb, partial, tokens, d_out, st);
+    if (dtype == DORA_F16) return compose_bwd_t<f16_t>(dy, inner, g, gm1, dz, dzb, partial, tokens, d_out, st);
+    return compose_bwd_t<float>(dy, inner, g, gm1, dz, dzb, partial, tokens, d_out, st);
 }
 
 hipError_t launch_dm_final(const float* partial, int slabs, const float* c, float eps, float* dm, int d_out, hipStream_t st)

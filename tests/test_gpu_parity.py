@@ -503,6 +503,65 @@ def test_fused_forward_rejects_fp32():
     assert e.value.status == 4
 
 
+# ----------------------------------------------------------------------------- LoRA dropout (App. B)
+
+DROPOUT_CASES = [SMALL[1], SMALL[3], SMALL[4], SMALL[7]]
+
+
+@pytest.mark.parametrize("cfg", DROPOUT_CASES, ids=[c.name for c in DROPOUT_CASES])
+def test_dropout_forward_and_backward(cfg):
+    # the adapter branch sees x_lora = dropout(x); the frozen layer's output stays that of x
+    mod = G.Module(cfg)
+    xl_s = I.dropped_input(cfg, mod.inp["x"], 0.25)
+    x_lora = G.to_dev(xl_s)
+    oi = oracle_inputs(mod)
+    f = O.forward(**oi, x_lora=I.to_f64(xl_s))
+    tol = G.TOL[cfg.dtype]["tensor"]
+    T, do, di, r = cfg.tokens, cfg.d_out, cfg.d_in, cfg.r
+    y, h, inner, c = G.empty((T, do), cfg.dtype), G.empty((T, r), cfg.dtype), G.empty((T, do), cfg.dtype), G.empty_f32(do)
+    D.dora_forward_dropout(mod.desc, mod.x, x_lora, mod.W, mod.A, mod.B, mod.m, None, None, y, h, inner, c,
+                           G.workspace(mod.desc, D.PHASE_FORWARD_DROPOUT))
+    G.assert_norm_close(G.to_f64(c), f["c"], G.TOL[cfg.dtype]["norm"])
+    for k, v in (("y", y), ("h", h), ("inner", inner)):
+        G.assert_close(k, G.to_f64(v), f[k], tol)
+    # the dropped input must really be used: the plain forward is far away
+    assert G.rel_fro(O.forward(**oi)["inner"], f["inner"]) > 0.1
+    b = O.backward_dropout(mod.f64("dy"), oi["x"], I.to_f64(xl_s), oi["W"], oi["A"], oi["B"], oi["m"], oi["s"], oi["eps"])
+    ws = G.workspace(mod.desc, D.PHASE_BACKWARD_DROPOUT)
+    for saved in (True, False):   # from the saved tensors, and with norm, h and inner recomputed from x_lora
+        dx, dxl = G.empty((T, di), cfg.dtype), G.empty((T, di), cfg.dtype)
+        dA, dB, dm = G.empty_f32(r, di), G.empty_f32(do, r), G.empty_f32(do)
+        D.dora_backward_dropout(mod.desc, mod.dy, x_lora, mod.W, mod.A, mod.B, mod.m, c if saved else None,
+                                h if saved else None, inner if saved else None, dx, dxl, dA, dB, dm, ws)
+        for k, v in (("dx", dx), ("dx_lora", dxl), ("dA", dA), ("dB", dB), ("dm", dm)):
+            G.assert_close(f"{k} [{'saved' if saved else 'recompute'}]", G.to_f64(v), b[k], tol)
+
+
+def test_dropout_entry_points_without_dropout_are_the_plain_module():
+    cfg = cfg_bf16("dropout_p0", 520, 392, 40, 300, seed=3)
+    mod = G.Module(cfg)
+    plain = mod.forward()
+    T, do, di, r = cfg.tokens, cfg.d_out, cfg.d_in, cfg.r
+    y, h, inner, c = G.empty((T, do), "bf16"), G.empty((T, r), "bf16"), G.empty((T, do), "bf16"), G.empty_f32(do)
+    D.dora_forward_dropout(mod.desc, mod.x, mod.x, mod.W, mod.A, mod.B, mod.m, None, None, y, h, inner, c,
+                           G.workspace(mod.desc, D.PHASE_FORWARD_DROPOUT))
+    for a, b_ in ((y, plain["y"]), (h, plain["h"]), (inner, plain["inner"])):
+        assert torch.equal(a.view(torch.int16), b_.view(torch.int16))
+    grads = mod.backward(w_norm=c, h=h, inner=inner)
+    dx, dxl = G.empty((T, di), "bf16"), G.empty((T, di), "bf16")
+    dA, dB, dm = G.empty_f32(r, di), G.empty_f32(do, r), G.empty_f32(do)
+    D.dora_backward_dropout(mod.desc, mod.dy, mod.x, mod.W, mod.A, mod.B, mod.m, c, h, inner, dx, dxl, dA, dB, dm,
+                            G.workspace(mod.desc, D.PHASE_BACKWARD_DROPOUT))
+    for k, v in (("dA", dA), ("dB", dB), ("dm", dm)):
+        assert torch.equal(v, grads[k]), k
+    G.assert_close("dx + dx_lora", G.to_f64(dx) + G.to_f64(dxl), G.to_f64(grads["dx"]), G.TOL["bf16"]["tensor"])
+    # a missing adapter input is an error, not a silent fall back to x
+    with pytest.raises(D.DoraError) as e:
+        D.dora_forward_dropout(mod.desc, mod.x, None, mod.W, mod.A, mod.B, mod.m, None, None, y, h, inner, c,
+                               G.workspace(mod.desc, D.PHASE_FORWARD_DROPOUT))
+    assert e.value.status == 1
+
+
 # ----------------------------------------------------------------------------- bias of the base layer
 
 @pytest.mark.parametrize("cfg", [SMALL[0], SMALL[2], SMALL[5], SMALL[6], SMALL[8]], ids=[IDS[0], IDS[2], IDS[5], IDS[6], IDS[8]])
