@@ -351,6 +351,7 @@ dora_status forward_contractions(const dora_desc* d, const void* x, const void* 
     Seg s1{xa ? xa : x, d_in, A, d_in, d_in};
     // (base and h are NOT paired into one launch: h's extra tiles would form a fifth, nearly empty
     // round behind the four full rounds of 256 x 256 base tiles and cost more than a launch of their own)
+    // (h after base, not before: it then finds part of x still in the memory-side cache; the other order costs 10 us)
     DORA_HIP(contract(d->dtype, true, true, T, d_out, &s0, 1, 1.f, base, d_out, false, DORA_K_GEMM_BASE, st));
     DORA_HIP(contract(d->dtype, true, true, T, r, &s1, 1, 1.f, h, r, false, DORA_K_GEMM_H, st));
     Seg s2{h, r, B, r, r};
@@ -384,7 +385,8 @@ size_t dora_workspace_bytes(const dora_desc* desc, int phase)
 {
     if (phase == DORA_PHASE_COMPOSE_BACKWARD) {
         if (check_desc(desc, false) != DORA_OK) return 0;
-        return up256((size_t)compose_bwd_slabs(desc->tokens, (int)desc->d_out, desc->dtype) * desc->d_out * sizeof(float));
+        const size_t n = up256((size_t)compose_bwd_slabs(desc->tokens, (int)desc->d_out, desc->dtype) * desc->d_out * sizeof(float));
+        return n > 0 ? n : 256;   // 0 is reserved for "invalid desc"
     }
     if (check_desc(desc, true) != DORA_OK) return 0;
     Bump b(nullptr);
@@ -527,7 +529,7 @@ dora_status dora_compose_backward(const dora_desc* desc, const void* dy, const v
     float* partial = nullptr;
     if (dm) {
         DORA_REQ_PTR(inner); DORA_REQ_PTR(w_norm);
-        size_t need = dora_workspace_bytes(desc, DORA_PHASE_COMPOSE_BACKWARD);
+        size_t need = up256((size_t)compose_bwd_slabs(desc->tokens, (int)desc->d_out, desc->dtype) * desc->d_out * sizeof(float));
         if ((st = check_ws(ws, ws_bytes, need)) != DORA_OK) return st;
         partial = (float*)ws;
     }

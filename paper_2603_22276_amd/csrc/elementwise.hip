@@ -193,12 +193,16 @@ __global__ __launch_bounds__(CW* CH) void compose_fwd_kernel(const T* base_, con
                                                               const float* __restrict__ g, const float* __restrict__ gm1,
                                                               const T* __restrict__ bias,  // added to out = base + delta only; may be null
                                                               float s, T* out_, T* inner_, int64_t tokens, int d_out,
-                                                              int rows_per_wg)
+                                                              int rows_per_wg, int col_blocks)
 {
     typedef Vec<T> V;
     typedef typename V::raw_t raw_t;
     constexpr int N = V::N;
-    const int col = (blockIdx.x * CW + threadIdx.x) * N;
+    // one-dimensional grid (no 65535 limit on either extent): consecutive workgroups take neighbouring
+    // column blocks of one row slab
+    const int col_block = blockIdx.x % col_blocks;
+    const int64_t slab = blockIdx.x / col_blocks;
+    const int col = (col_block * CW + threadIdx.x) * N;
     if (col >= d_out) return;
     float gv[N], g1[N], bv[N];
 #pragma unroll
@@ -208,7 +212,7 @@ __global__ __launch_bounds__(CW* CH) void compose_fwd_kernel(const T* base_, con
         bv[i] = 0.f;
     }
     if ((OUTMODE == 1 || OUTMODE == 3) && bias) V::unpack(*reinterpret_cast<const raw_t*>(bias + col), bv);
-    const int64_t row_begin = (int64_t)blockIdx.y * rows_per_wg;
+    const int64_t row_begin = slab * rows_per_wg;
     int64_t row_end = row_begin + rows_per_wg;
     if (row_end > tokens) row_end = tokens;
     constexpr int UNROLL = 4;
@@ -253,13 +257,15 @@ __global__ __launch_bounds__(CW* CH) void compose_bwd_kernel(const T* __restrict
                                                               const float* __restrict__ g, const float* __restrict__ gm1,
                                                               T* __restrict__ dz_, T* __restrict__ dzb_,
                                                               float* __restrict__ partial, int64_t tokens, int d_out,
-                                                              int rows_per_wg)
+                                                              int rows_per_wg, int col_blocks)
 {
     typedef Vec<T> V;
     typedef typename V::raw_t raw_t;
     constexpr int N = V::N;
     __shared__ float red[CH][CW * N];
-    const int col = (blockIdx.x * CW + threadIdx.x) * N;
+    const int col_block = blockIdx.x % col_blocks;
+    const int64_t slab = blockIdx.x / col_blocks;
+    const int col = (col_block * CW + threadIdx.x) * N;
     const bool active = col < d_out;
     float gv[N], g1[N], acc[N];
 #pragma unroll
@@ -268,7 +274,7 @@ __global__ __launch_bounds__(CW* CH) void compose_bwd_kernel(const T* __restrict
         g1[i] = (SPLIT && active) ? gm1[col + i] : 0.f;
         acc[i] = 0.f;
     }
-    const int64_t row_begin = (int64_t)blockIdx.y * rows_per_wg;
+    const int64_t row_begin = slab * rows_per_wg;
     int64_t row_end = row_begin + rows_per_wg;
     if (row_end > tokens) row_end = tokens;
     constexpr int UNROLL = 4;
@@ -321,7 +327,7 @@ __global__ __launch_bounds__(CW* CH) void compose_bwd_kernel(const T* __restrict
             for (int i = 0; i < N; ++i) {
                 float v = red[0][threadIdx.x * N + i];
                 for (int y = 1; y < CH; ++y) v += red[y][threadIdx.x * N + i];  // fixed order
-                partial[(int64_t)blockIdx.y * d_out + col + i] = v;
+                partial[slab * d_out + col + i] = v;
             }
         }
     }
@@ -428,14 +434,15 @@ static hipError_t compose_fwd_t(const void* base, const void* lora, const float*
     constexpr int N = Vec<T>::N;
     int cpr = d_out / N;
     const int FWD_ROWS_PER_WG = slab_rows(128, tokens, d_out, sizeof(T) == 2 ? DORA_BF16 : DORA_F32);
-    dim3 grid((cpr + CW - 1) / CW, (unsigned)((tokens + FWD_ROWS_PER_WG - 1) / FWD_ROWS_PER_WG));
+    const int col_blocks = (cpr + CW - 1) / CW;
+    dim3 grid((unsigned)(col_blocks * ((tokens + FWD_ROWS_PER_WG - 1) / FWD_ROWS_PER_WG)));
     dim3 block(CW, CH);
     const T* b = (const T*)base;
     const T* l = (const T*)lora;
     T* o = (T*)out;
     T* in = (T*)inner;
 #define DORA_LAUNCH_FWD(D, I) \
-    compose_fwd_kernel<T, D, I><<<grid, block, 0, st>>>(b, l, g, gm1, (const T*)bias, s, o, in, tokens, d_out, FWD_ROWS_PER_WG)
+    compose_fwd_kernel<T, D, I><<<grid, block, 0, st>>>(b, l, g, gm1, (const T*)bias, s, o, in, tokens, d_out, FWD_ROWS_PER_WG, col_blocks)
     if (!out) { DORA_LAUNCH_FWD(0, true); }
     else if (write_delta == 2) { if (inner) DORA_LAUNCH_FWD(3, true); else DORA_LAUNCH_FWD(3, false); }
     else if (write_delta) { if (inner) DORA_LAUNCH_FWD(2, true); else DORA_LAUNCH_FWD(2, false); }
@@ -473,11 +480,12 @@ static hipError_t compose_bwd_t(const void* dy, const void* inner, const float* 
     int cpr = d_out / N;
     const int dtype = sizeof(T) == 2 ? DORA_BF16 : DORA_F32;
     const int BWD_ROWS_PER_WG = compose_bwd_rows(tokens, d_out, dtype);
-    dim3 grid((cpr + CW - 1) / CW, (unsigned)compose_bwd_slabs(tokens, d_out, dtype));
+    const int col_blocks = (cpr + CW - 1) / CW;
+    dim3 grid((unsigned)((int64_t)col_blocks * compose_bwd_slabs(tokens, d_out, dtype)));
     dim3 block(CW, CH);
 #define DORA_LAUNCH_BWD(DM, SP)                                                                                   \
     compose_bwd_kernel<T, DM, SP><<<grid, block, 0, st>>>((const T*)dy, (const T*)inner, g, gm1, (T*)dz, (T*)dzb, partial, \
-                                                           tokens, d_out, BWD_ROWS_PER_WG)
+                                                           tokens, d_out, BWD_ROWS_PER_WG, col_blocks)
     if (partial) { if (dzb) DORA_LAUNCH_BWD(true, true); else DORA_LAUNCH_BWD(true, false); }
     else { if (dzb) DORA_LAUNCH_BWD(false, true); else DORA_LAUNCH_BWD(false, false); }
 #undef DORA_LAUNCH_BWD

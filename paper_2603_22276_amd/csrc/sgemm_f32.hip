@@ -17,7 +17,8 @@ __global__ __launch_bounds__(256) void sgemm_f32_kernel(SgemmArgs p)
     __shared__ float Bs[TK][TS + 1];
     const int tid = threadIdx.x;
     const int tx = tid % 16, ty = tid / 16;
-    const int m0 = blockIdx.y * TS, n0 = blockIdx.x * TS;
+    const int tiles_n = (p.N + TS - 1) / TS;   // one-dimensional grid: no 65535 limit on the row-tile count
+    const int m0 = (int)(blockIdx.x / tiles_n) * TS, n0 = (int)(blockIdx.x % tiles_n) * TS;
     float acc[TT][TT];
 #pragma unroll
     for (int i = 0; i < TT; ++i)
@@ -70,7 +71,7 @@ hipError_t launch_sgemm_f32(const SgemmArgs& a, int trace_id, hipStream_t stream
 {
     if (a.M == 0 || a.N == 0) return hipSuccess;
     TraceScope ts(trace_id, stream);
-    dim3 grid((a.N + TS - 1) / TS, (a.M + TS - 1) / TS);
+    dim3 grid((unsigned)(((a.N + TS - 1) / TS) * (int64_t)((a.M + TS - 1) / TS)));
     sgemm_f32_kernel<<<grid, dim3(256), 0, stream>>>(a);
     return hipGetLastError();
 }

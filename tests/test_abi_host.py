@@ -54,6 +54,11 @@ def test_workspace_sizes():
     assert D.dora_workspace_bytes(desc(d_out=250), D.PHASE_NORM) == 0       # not a multiple of 8
     assert D.dora_workspace_bytes(desc(dtype=7), D.PHASE_NORM) == 0
     assert D.dora_workspace_bytes(d, 99) == 0
+    # a valid desc never sizes to 0 (0 means "invalid desc"), not even with no tokens
+    assert D.dora_workspace_bytes(desc(tokens=0), D.PHASE_COMPOSE_BACKWARD) == 256
+    assert D.dora_workspace_bytes(desc(tokens=0), D.PHASE_BACKWARD) >= 256
+    # millions of tokens on a narrow module: row slabs no longer ride on a 65535-limited grid axis
+    assert D.dora_workspace_bytes(desc(d_out=64, tokens=4_000_000, d_in=8, r=8), D.PHASE_BACKWARD) > 0
 
 
 def call(fn, *args):

@@ -336,6 +336,31 @@ def test_compose_backward(dtype, tokens, d_out):
     assert torch.equal(dz2.view(torch.uint8), dz.view(torch.uint8))
 
 
+def test_compose_passes_on_millions_of_tokens_of_a_narrow_module():
+    # 9 million tokens x 8 outputs: 70313 row slabs of 128, beyond what a 65535-limited grid axis could carry
+    tokens, d_out = 9_000_000, 8
+    rng = np.random.default_rng(99)
+    base_s = I.quantise(rng.standard_normal((tokens, d_out), dtype=np.float32), "bf16")
+    lora_s = I.quantise(rng.standard_normal((tokens, d_out), dtype=np.float32) * 0.02, "bf16")
+    g32 = (1 + 0.0015 * rng.standard_normal(d_out)).astype(np.float32)
+    c32 = np.ones(d_out, np.float32)
+    desc = D.make_desc(d_out, 8, 8, tokens, D.DORA_BF16, 1.5)
+    base, lora = G.to_dev(base_s), G.to_dev(lora_s)
+    y, inner = G.empty((tokens, d_out), "bf16"), G.empty((tokens, d_out), "bf16")
+    D.dora_compose(desc, base, lora, G.to_dev(g32), None, y, 0, inner)
+    rows = np.concatenate([np.arange(300), rng.integers(0, tokens, 5000), np.arange(tokens - 300, tokens)])
+    b64, l64 = I.to_f64(base_s[rows]), I.to_f64(lora_s[rows])
+    ridx = torch.from_numpy(rows).to(y.device)
+    G.assert_close("y[rows]", G.to_f64(y[ridx]), b64 + O.compose_delta(b64, l64, g32.astype(np.float64), 1.5), 2e-2)
+    assert bool(torch.isfinite(y.float()).all())       # every slab was written
+    dz, dm = G.empty((tokens, d_out), "bf16"), G.empty_f32(d_out)
+    ws = G.workspace(desc, D.PHASE_COMPOSE_BACKWARD)
+    D.dora_compose_backward(desc, base, inner, G.to_dev(g32), G.to_dev(c32), dz, dm, ws)
+    assert bool(torch.isfinite(dz.float()).all())
+    ref_dm = np.einsum("tj,tj->j", I.to_f64(base_s), G.to_f64(inner))
+    G.assert_close("dm", G.to_f64(dm), ref_dm, 1e-4)
+
+
 # ----------------------------------------------------------------------------- contractions (a7, a8)
 
 @pytest.mark.parametrize("cfg", SMALL, ids=IDS)
