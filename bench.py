@@ -225,12 +225,15 @@ def time_steps(torch, fn, steps):
 
 
 def kernel_table(D, torch, wl, reps, dominant_live):
-    """Every launch bracketed by HIP events, module by module, so that each kernel's time can be priced with the
-    algorithmic work of the module it ran for.  Returns the per-kernel list and the summed contraction rate."""
+    """Per-kernel durations and roofline fractions.  Two passes with every launch bracketed by HIP events:
+    one module at a time, to learn how many launches of each kernel a module's forward and backward make (each
+    launch is priced with the algorithmic work of the module it ran for), then `reps` whole steps back to back,
+    whose summed durations per kernel are the ones reported (a kernel timed right after an idle gap runs slower
+    than inside the sequence).  Returns the per-kernel list and the summed contraction rate."""
     names = [D.dora_trace_name(k) for k in range(N_KERNEL_IDS)]
     tot = {n: {"ms": 0.0, "launches": 0, "flops": 0.0, "bytes": 0.0} for n in names}
 
-    def traced(fn, work):
+    def traced(fn):
         D.dora_trace_reset()
         D.dora_trace_select(~0)
         D.dora_trace_enable(True)
@@ -238,25 +241,34 @@ def kernel_table(D, torch, wl, reps, dominant_live):
         torch.cuda.synchronize()
         D.dora_trace_enable(False)
         D.dora_trace_collect()
-        got = {n: D.dora_trace_get(k) for k, n in enumerate(names)}
+        return {n: D.dora_trace_get(k) for k, n in enumerate(names)}
+
+    def price(got, work):
         w = dict(work)
         # launches that carry two contractions at once are priced with the work of both
-        if got["gemm_dA"][1] > 0 and got["gemm_dB"][1] == 0 and "gemm_dA" in w:
+        if got["gemm_dA"][1] > 0 and got["gemm_dB"][1] == 0:
             w["gemm_dA"] = (w["gemm_dA"][0] + w["gemm_dB"][0], w["gemm_dA"][1] + w["gemm_dB"][1])
-        for n, (ms, cnt) in got.items():
+        for n, (_, cnt) in got.items():
             if cnt and n in w:
-                tot[n]["ms"] += ms
-                tot[n]["launches"] += cnt
                 tot[n]["flops"] += w[n][0] * cnt
                 tot[n]["bytes"] += w[n][1] * cnt
 
-    for _ in range(reps):
-        for m in wl.modules:
-            traced(m.forward, kernel_work(m.cfg, inner_saved=(m.mode == "fwd_bwd_saved")))
-        for m in reversed(wl.modules):
-            if m.mode != "fwd":
-                traced(m.backward, kernel_work(m.cfg, inner_saved=False))
-    fp32 = wl.modules[0].cfg.dtype != "bf16"
+    seen = {}
+    for m in wl.modules:   # modules of one shape and phase make the same launches: trace one of each kind
+        key = (m.cfg.d_out, m.cfg.d_in, m.cfg.r, m.cfg.tokens, m.cfg.dtype, m.mode)
+        if key not in seen:
+            seen[key] = (traced(m.forward), traced(m.backward) if m.mode != "fwd" else None)
+        f, b = seen[key]
+        price(f, kernel_work(m.cfg, inner_saved=(m.mode == "fwd_bwd_saved")))
+        if b is not None:
+            price(b, kernel_work(m.cfg, inner_saved=False))
+
+    def whole():
+        for _ in range(reps):
+            wl.step()
+    for n, (ms, cnt) in traced(whole).items():
+        tot[n]["ms"], tot[n]["launches"] = ms, cnt
+    fp32 = wl.modules[0].cfg.dtype == "f32"
     kernels = []
     for n in names:
         t = tot[n]
@@ -265,19 +277,20 @@ def kernel_table(D, torch, wl, reps, dominant_live):
         live = dominant_live.get(n)
         ms, cnt = (live if live and live[1] > 0 else (t["ms"], t["launches"]))
         secs = ms * 1e-3 * (t["launches"] / cnt)          # total time of this kernel's launches in `reps` steps
+        flops, nbytes = t["flops"] * reps, t["bytes"] * reps
         hbm = n in HBM_BOUND
         if hbm:
-            bound, ach, peak, unit = "hbm", t["bytes"] / secs / 1e9, PEAK_HBM_GBS, "GB/s"
+            bound, ach, peak, unit = "hbm", nbytes / secs / 1e9, PEAK_HBM_GBS, "GB/s"
         elif fp32:
-            bound, ach, peak, unit = "alu", t["flops"] / secs / 1e12, PEAK_FP32_TFLOPS, "TFLOP/s"
+            bound, ach, peak, unit = "alu", flops / secs / 1e12, PEAK_FP32_TFLOPS, "TFLOP/s"
         else:
-            bound, ach, peak, unit = "mfma", t["flops"] / secs / 1e12, PEAK_BF16_TFLOPS, "TFLOP/s"
+            bound, ach, peak, unit = "mfma", flops / secs / 1e12, PEAK_BF16_TFLOPS, "TFLOP/s"
         kernels.append({"kernel": n, "launches_per_step": t["launches"] / reps, "avg_us": secs / t["launches"] * 1e6,
                         "us_per_step": secs / reps * 1e6, "bound": bound, "achieved": ach, "peak": peak, "unit": unit,
-                        "frac": ach / peak, "gbytes_per_s_algorithmic": t["bytes"] / secs / 1e9,
+                        "frac": ach / peak, "gbytes_per_s_algorithmic": nbytes / secs / 1e9,
                         "timed": "inside the timed steps" if live and live[1] > 0 else "separate pass, every launch bracketed"})
     contr = [k for k in kernels if k["bound"] in ("mfma", "alu") and tot[k["kernel"]]["flops"] > 0]
-    flops = sum(tot[k["kernel"]]["flops"] for k in contr) / reps
+    flops = sum(tot[k["kernel"]]["flops"] for k in contr)
     secs = sum(k["us_per_step"] for k in contr) * 1e-6
     return kernels, (flops / secs / 1e12 if secs > 0 else None)
 
@@ -456,7 +469,7 @@ def measure(wl, args, torch, D, extras):
     peak_mem = int(torch.cuda.max_memory_allocated())
     if len(wl.modules) > 1:
         live = {}   # several shapes share a kernel id: the per-module pass below prices each launch with its own work
-    reps = args.steps if len(wl.modules) == 1 else 1
+    reps = args.steps if len(wl.modules) == 1 else min(args.steps, 3)
     kernels, contr_rate = kernel_table(D, torch, wl, reps, live)
     dom = max(kernels, key=lambda k: k["us_per_step"])
     traffic, tinfo = hbm_traffic(wl.name, dom["kernel"])

@@ -10,12 +10,23 @@ namespace dora {
 
 namespace {
 
-constexpr int CW = 64;  // threads along the column direction (one 16-byte vector each)
-constexpr int CH = 4;   // threads along the row direction
+// Block shape of the compose passes: CW threads along the column direction (one 16-byte vector each), CH along
+// the row direction, CW * CH = 256.  Measured inside the forward + backward sequence at 8192 x 8192: the forward
+// pass (two tensors updated in place) is fastest with one thread row spanning 4 KB of every row it touches
+// (256 x 1: 85 us against 95 us for 64 x 4); the backward pass (three separate streams) with 64 x 4 and short
+// slabs (70 us against 83 / 95 us for 128 x 2 / 256 x 1).  The two passes are not independent: what the forward
+// pass leaves behind in the memory system moves the backward pass by several microseconds, so they were tuned
+// together, inside the sequence.
+constexpr int BWD_CW = 64, BWD_CH = 4;
 
-// 16-byte store with the non-temporal hint: the compose outputs are written once and not re-read by
-// the writing kernel; on this part the hint lifts a 2-read/2-write stream from ~5.4 to ~6.9 TB/s.
+// 16-byte store with the non-temporal hint, for outputs nothing reads soon; on this part the hint lifts a
+// 2-read/2-write stream from ~5.4 to ~6.9 TB/s in isolation.
 typedef unsigned int u32x4_nt_t __attribute__((ext_vector_type(4)));
+template <typename R>
+__device__ __forceinline__ void store_plain(void* p, const R& v)
+{
+    *reinterpret_cast<R*>(p) = v;
+}
 template <typename R>
 __device__ __forceinline__ void store_stream(void* p, const R& v)
 {
@@ -187,7 +198,7 @@ __global__ void rownorm_s0_16_kernel(const T* __restrict__ W, float* __restrict_
 // OUTMODE: 0 = no out tensor (inner only), 1 = out = base + delta, 2 = out = delta, 3 = out += delta (the
 // frozen layer's output is already in out and base is the adapter branch's own base, App. B "Chunked
 // dropout path").
-template <typename T, int OUTMODE, bool INNER>
+template <typename T, int OUTMODE, bool INNER, int CW, int CH>
 __global__ __launch_bounds__(CW* CH) void compose_fwd_kernel(const T* base_, const T* lora_,  // out may alias base, inner may alias lora
                                                              
                                                               const float* __restrict__ g, const float* __restrict__ gm1,
@@ -242,8 +253,10 @@ __global__ __launch_bounds__(CW* CH) void compose_fwd_kernel(const T* base_, con
                     of[i] = (OUTMODE == 2) ? delta : (((OUTMODE == 3) ? yf[i] : bf[i]) + delta) + bv[i];
                     inf[i] = sl + bf[i];
                 }
+                // y leaves with the streaming hint; inner with a plain store, so that the pass that reads it next (the
+                // compose backward of the same module, right away when inner was recomputed) can find it in cache
                 if (OUTMODE != 0) store_stream(out_ + rr * d_out + col, V::pack(of));
-                if (INNER) store_stream(inner_ + rr * d_out + col, V::pack(inf));
+                if (INNER) store_plain(inner_ + rr * d_out + col, V::pack(inf));
             }
         }
     }
@@ -252,7 +265,7 @@ __global__ __launch_bounds__(CW* CH) void compose_fwd_kernel(const T* base_, con
 // Compose backward: dz = g*dy, and (DM) the first stage of the column sum of dy*inner over this slab.
 // SPLIT: also dzb = (g-1)*dy, the gradient reaching the adapter branch's own base when that branch has an
 // input of its own (dz then reaches lora only, scaled by s in the products that follow).
-template <typename T, bool DM, bool SPLIT>
+template <typename T, bool DM, bool SPLIT, int CW, int CH>
 __global__ __launch_bounds__(CW* CH) void compose_bwd_kernel(const T* __restrict__ dy_, const T* __restrict__ inner_,
                                                               const float* __restrict__ g, const float* __restrict__ gm1,
                                                               T* __restrict__ dz_, T* __restrict__ dzb_,
@@ -277,45 +290,58 @@ __global__ __launch_bounds__(CW* CH) void compose_bwd_kernel(const T* __restrict
     const int64_t row_begin = slab * rows_per_wg;
     int64_t row_end = row_begin + rows_per_wg;
     if (row_end > tokens) row_end = tokens;
-    constexpr int UNROLL = 4;
+    constexpr int UNROLL = 4, STEP = CH * UNROLL;
     if (active) {
-        // software prefetch: the loads of batch b+1 are issued before batch b is reduced and
-        // stored, so every wave keeps UNROLL * 2 vectors in flight from start to finish
-        raw_t d[UNROLL], in[UNROLL], dn[UNROLL], inn[UNROLL];
-        auto load_batch = [&](int64_t row, raw_t (&dd)[UNROLL], raw_t (&ii)[UNROLL]) {
+        // Two register sets used in turn (no copies between them): the loads of batch b+1 are in flight while
+        // batch b is reduced and stored.  Batches that lie wholly inside the slab take loads and stores without
+        // per-row conditions, so the waits the compiler places count exactly the loads still outstanding.
+        raw_t da[UNROLL], ia[UNROLL], db[UNROLL], ib[UNROLL];
+        auto load_full = [&](int64_t row, raw_t (&dd)[UNROLL], raw_t (&ii)[UNROLL]) {
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
-                int64_t rr = row + u * CH;
-                if (rr < row_end) {
-                    dd[u] = *reinterpret_cast<const raw_t*>(dy_ + rr * d_out + col);
-                    if (DM) ii[u] = *reinterpret_cast<const raw_t*>(inner_ + rr * d_out + col);
-                }
+                const int64_t rr = row + u * CH;
+                dd[u] = *reinterpret_cast<const raw_t*>(dy_ + rr * d_out + col);
+                if (DM) ii[u] = *reinterpret_cast<const raw_t*>(inner_ + rr * d_out + col);
             }
         };
-        int64_t row = row_begin + threadIdx.y;
-        load_batch(row, d, in);
-        for (; row < row_end; row += CH * UNROLL) {
-            const int64_t next = row + CH * UNROLL;
-            if (next < row_end) load_batch(next, dn, inn);
+        auto row_work = [&](int64_t rr, const raw_t& dv, const raw_t& iv) {
+            float df[N], nf[N], zf[N], zb[N];
+            V::unpack(dv, df);
+            if (DM) V::unpack(iv, nf);
 #pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
-                int64_t rr = row + u * CH;
-                if (rr < row_end) {
-                    float df[N], nf[N], zf[N], zb[N];
-                    V::unpack(d[u], df);
-                    if (DM) V::unpack(in[u], nf);
-#pragma unroll
-                    for (int i = 0; i < N; ++i) {
-                        zf[i] = gv[i] * df[i];
-                        if (SPLIT) zb[i] = g1[i] * df[i];
-                        if (DM) acc[i] = fmaf(df[i], nf[i], acc[i]);
-                    }
-                    store_stream(dz_ + rr * d_out + col, V::pack(zf));
-                    if (SPLIT) store_stream(dzb_ + rr * d_out + col, V::pack(zb));
-                }
+            for (int i = 0; i < N; ++i) {
+                zf[i] = gv[i] * df[i];
+                if (SPLIT) zb[i] = g1[i] * df[i];
+                if (DM) acc[i] = fmaf(df[i], nf[i], acc[i]);
             }
+            store_stream(dz_ + rr * d_out + col, V::pack(zf));   // (a plain store here slows the dh product by 14 us)
+            if (SPLIT) store_stream(dzb_ + rr * d_out + col, V::pack(zb));
+        };
+        auto work_full = [&](int64_t row, const raw_t (&dd)[UNROLL], const raw_t (&ii)[UNROLL]) {
 #pragma unroll
-            for (int u = 0; u < UNROLL; ++u) { d[u] = dn[u]; if (DM) in[u] = inn[u]; }
+            for (int u = 0; u < UNROLL; ++u) row_work(row + u * CH, dd[u], ii[u]);
+        };
+        const int nfull = (int)((row_end - row_begin) / STEP);   // uniform over the workgroup
+        int64_t row = row_begin + threadIdx.y;
+        if (nfull > 0) load_full(row, da, ia);
+        for (int b = 0; b < nfull; b += 2) {
+            if (b + 1 < nfull) load_full(row + STEP, db, ib);
+            work_full(row, da, ia);
+            row += STEP;
+            if (b + 1 >= nfull) break;
+            if (b + 2 < nfull) load_full(row + STEP, da, ia);
+            work_full(row, db, ib);
+            row += STEP;
+        }
+        // ragged end of the slab (fewer than STEP rows)
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int64_t rr = row + u * CH;
+            if (rr < row_end) {
+                raw_t dv = *reinterpret_cast<const raw_t*>(dy_ + rr * d_out + col), iv = dv;
+                if (DM) iv = *reinterpret_cast<const raw_t*>(inner_ + rr * d_out + col);
+                row_work(rr, dv, iv);
+            }
         }
     }
     if (DM) {
@@ -414,10 +440,9 @@ hipError_t launch_rownorm_f32(const float* W, const float* base_in, const float*
     return hipGetLastError();
 }
 
-// Rows per workgroup.  Measured inside the whole forward + backward sequence (where these passes
-// start at the clock the preceding contraction left behind) long slabs win: 128 rows forward, 64
-// backward; shorter ones are chosen only when the launch would otherwise leave CUs without work.
-static int slab_rows(int preferred, int64_t tokens, int d_out, int dtype)
+// Rows per workgroup: 128 forward, 32 backward (measured inside the whole forward + backward sequence);
+// shorter ones are chosen only when the launch would otherwise leave CUs without work.
+static int slab_rows(int preferred, int64_t tokens, int d_out, int dtype, int CW)
 {
     const int n = dtype == DORA_F32 ? 4 : 8;
     const int64_t col_blocks = (d_out / n + CW - 1) / CW;
@@ -433,7 +458,9 @@ static hipError_t compose_fwd_t(const void* base, const void* lora, const float*
 {
     constexpr int N = Vec<T>::N;
     int cpr = d_out / N;
-    const int FWD_ROWS_PER_WG = slab_rows(128, tokens, d_out, sizeof(T) == 2 ? DORA_BF16 : DORA_F32);
+    // the widest block that leaves no thread without a column
+    const int CW = cpr >= 256 ? 256 : (cpr >= 128 ? 128 : 64), CH = 256 / CW;
+    const int FWD_ROWS_PER_WG = slab_rows(128, tokens, d_out, sizeof(T) == 2 ? DORA_BF16 : DORA_F32, CW);
     const int col_blocks = (cpr + CW - 1) / CW;
     dim3 grid((unsigned)(col_blocks * ((tokens + FWD_ROWS_PER_WG - 1) / FWD_ROWS_PER_WG)));
     dim3 block(CW, CH);
@@ -441,13 +468,20 @@ static hipError_t compose_fwd_t(const void* base, const void* lora, const float*
     const T* l = (const T*)lora;
     T* o = (T*)out;
     T* in = (T*)inner;
-#define DORA_LAUNCH_FWD(D, I) \
-    compose_fwd_kernel<T, D, I><<<grid, block, 0, st>>>(b, l, g, gm1, (const T*)bias, s, o, in, tokens, d_out, FWD_ROWS_PER_WG, col_blocks)
+#define DORA_LAUNCH_FWD_S(D, I, W_, H_) \
+    compose_fwd_kernel<T, D, I, W_, H_><<<grid, block, 0, st>>>(b, l, g, gm1, (const T*)bias, s, o, in, tokens, d_out, FWD_ROWS_PER_WG, col_blocks)
+#define DORA_LAUNCH_FWD(D, I)                                        \
+    do {                                                             \
+        if (CW == 256) DORA_LAUNCH_FWD_S(D, I, 256, 1);              \
+        else if (CW == 128) DORA_LAUNCH_FWD_S(D, I, 128, 2);         \
+        else DORA_LAUNCH_FWD_S(D, I, 64, 4);                         \
+    } while (0)
     if (!out) { DORA_LAUNCH_FWD(0, true); }
     else if (write_delta == 2) { if (inner) DORA_LAUNCH_FWD(3, true); else DORA_LAUNCH_FWD(3, false); }
     else if (write_delta) { if (inner) DORA_LAUNCH_FWD(2, true); else DORA_LAUNCH_FWD(2, false); }
     else { if (inner) DORA_LAUNCH_FWD(1, true); else DORA_LAUNCH_FWD(1, false); }
 #undef DORA_LAUNCH_FWD
+#undef DORA_LAUNCH_FWD_S
     return hipGetLastError();
 }
 
@@ -464,7 +498,7 @@ hipError_t launch_compose_fwd(int dtype, const void* base, const void* lora, con
     return compose_fwd_t<float>(base, lora, g, gm1, bias, s, out, write_delta, inner, tokens, d_out, st);
 }
 
-static int compose_bwd_rows(int64_t tokens, int d_out, int dtype) { return slab_rows(64, tokens, d_out, dtype); }
+static int compose_bwd_rows(int64_t tokens, int d_out, int dtype) { return slab_rows(32, tokens, d_out, dtype, BWD_CW); }
 
 int compose_bwd_slabs(int64_t tokens, int d_out, int dtype)
 {
@@ -480,11 +514,11 @@ static hipError_t compose_bwd_t(const void* dy, const void* inner, const float* 
     int cpr = d_out / N;
     const int dtype = sizeof(T) == 2 ? DORA_BF16 : DORA_F32;
     const int BWD_ROWS_PER_WG = compose_bwd_rows(tokens, d_out, dtype);
-    const int col_blocks = (cpr + CW - 1) / CW;
+    const int col_blocks = (cpr + BWD_CW - 1) / BWD_CW;
     dim3 grid((unsigned)((int64_t)col_blocks * compose_bwd_slabs(tokens, d_out, dtype)));
-    dim3 block(CW, CH);
+    dim3 block(BWD_CW, BWD_CH);
 #define DORA_LAUNCH_BWD(DM, SP)                                                                                   \
-    compose_bwd_kernel<T, DM, SP><<<grid, block, 0, st>>>((const T*)dy, (const T*)inner, g, gm1, (T*)dz, (T*)dzb, partial, \
+    compose_bwd_kernel<T, DM, SP, BWD_CW, BWD_CH><<<grid, block, 0, st>>>((const T*)dy, (const T*)inner, g, gm1, (T*)dz, (T*)dzb, partial, \
                                                            tokens, d_out, BWD_ROWS_PER_WG, col_blocks)
     if (partial) { if (dzb) DORA_LAUNCH_BWD(true, true); else DORA_LAUNCH_BWD(true, false); }
     else { if (dzb) DORA_LAUNCH_BWD(false, true); else DORA_LAUNCH_BWD(false, false); }
