@@ -308,7 +308,7 @@ def oracle_cores():
 
 def cpu_baseline(samples, backward, note):
     """The fp64 oracle, as it stands, on `samples` = [(cfg, stored host arrays, sample tokens)], repeated until
-    about ten seconds of CPU work are on the clock (at most 8 passes)."""
+    about ten seconds of CPU work are on the clock."""
     import numpy as np
     from oracle import dora_oracle as O
     from paper_2603_22276_amd import inputs as I
@@ -320,7 +320,7 @@ def cpu_baseline(samples, backward, note):
                          I.to_f64(inp["dy"][:n]) if backward else None, np.asarray(inp["m"], dtype=np.float64),
                          float(inp["s"])))
     reps, dt = 0, 0.0
-    while reps < 8 and dt < 10.0:
+    while dt < 10.0 and reps < 5000:
         t0 = time.perf_counter()
         for cfg, n, W, A, B, x, dy, m, s in prepared:
             f = O.forward(x, W, A, B, m, s, cfg.eps)
