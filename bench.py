@@ -38,7 +38,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 HBM_BOUND = {"compose_fwd", "compose_bwd", "mag_scale"}
 K_BASE, K_DX, K_FUSED = 6, 13, 18
-N_KERNEL_IDS = 19
+N_KERNEL_IDS = 20
 METRIC_FMT = "DoRA {phase} tokens/s at d_in={d_in} r={r} {dtype}; %MFMA and %HBM peak"
 
 
@@ -66,6 +66,7 @@ def kernel_work(cfg, inner_saved=True):
         "gemm_dA": (2.0 * r * di * T, e * (T * r + T * di) + 4 * r * di),
         "gemm_dB": (2.0 * do * r * T, e * (T * do + T * r) + 4 * do * r),
         "gemm_fused_fwd": (2.0 * T * do * (di + r), e * (T * di + do * di + T * r + do * r + 2 * T * do)),
+        "splitk_reduce": (0.0, 0.0),   # the work of a split product is priced on its GEMM launch
     }
 
 

@@ -169,7 +169,8 @@ dora_status dora_compose_backward(const dora_desc* desc, const void* dy, const v
 /*
  * The three forward contractions on their own (App. A item 1): base = x W^T [tokens, d_out],
  * h = x A^T [tokens, r], lora = h B^T [tokens, d_out], each rounded once to `dtype`.
- * Exactly the launches dora_forward makes for these steps.  Needs no workspace.
+ * The launches dora_forward makes for these steps, except that without a workspace h = x A^T is never
+ * split along K (dora_forward splits it when its tiles would leave most of the chip idle).  Needs no workspace.
  */
 dora_status dora_project(const dora_desc* desc, const void* x, const void* W, const void* A, const void* B,
                          void* base, void* h, void* lora, void* stream);

@@ -43,7 +43,8 @@ enum {
     DORA_K_PROBE_COPY = 16,  /* dora_probe_copy                                        */
     DORA_K_PROBE_MFMA = 17,  /* dora_probe_mfma                                        */
     DORA_K_GEMM_FUSED_FWD = 18, /* y = g (.) ([s*h | x] [B | W]^T), dora_forward_fused  */
-    DORA_K_COUNT = 19
+    DORA_K_SPLITK_REDUCE = 19,  /* fixed-order sum of the K slices of a skinny product    */
+    DORA_K_COUNT = 20
 };
 void dora_trace_enable(int on);
 void dora_trace_select(uint64_t kernel_mask); /* bit k set = bracket launches of kernel id k (default: all) */

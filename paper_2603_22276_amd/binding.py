@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(HERE, "libdora.so")
 
 DORA_F32, DORA_BF16, DORA_F16 = 0, 1, 2
 PHASE_NORM, PHASE_FORWARD, PHASE_BACKWARD, PHASE_BACKWARD_RECOMPUTE, PHASE_COMPOSE_BACKWARD, PHASE_FORWARD_DROPOUT, PHASE_BACKWARD_DROPOUT = range(7)
-K_COUNT = 19
+K_COUNT = 20
 
 EXPORTS = (
     "dora_workspace_bytes", "dora_norm", "dora_norm_static", "dora_norm_static_max_bytes", "dora_base_sq", "dora_norm_cached", "dora_norm_terms", "dora_norm_assemble", "dora_mag_scale", "dora_compose", "dora_compose_backward",

@@ -180,6 +180,11 @@ hipError_t launch_rownorm_s0_16(const bf16_t* W, int dt, float* c, int d_out, in
 hipError_t launch_rownorm_f32(const float* W, const float* base_in, const float* B, const float* U, const float* BG,
                               double s, float* c, float* terms, int d_out, int d_in, int r, bool squared, hipStream_t st);
 
+// out[i] = sum over z (in order) of partials[z * n + i], written in the storage dtype; out2 (may be nullptr)
+// receives alpha2 times the same sum.  n a multiple of 8.
+hipError_t launch_splitk_reduce(const float* partials, int ksplit, int64_t n, int dtype, void* out, float alpha2, void* out2,
+                                hipStream_t st);
+
 hipError_t launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t st);
 hipError_t launch_mfma_probe(float* sink, int iters, int workgroups, hipStream_t st);
 

@@ -187,6 +187,21 @@ void plan_norm(const dora_desc* d, Bump& b, NormPlan& n)
     }
 }
 
+// Split of K for the skinny products with a 16-bit output (h = x A^T, dh = s dz B): with [tokens, r] outputs of
+// 128 x 128 tiles a launch at 4096 tokens has 96 workgroups for 256 CUs.  When at most half the CUs would have
+// work, K is cut into slices (fp32 partials in the workspace, summed in slice order by a small reduce launch) so
+// that the launch approaches one workgroup per CU, each slice keeping at least 16 K steps.
+inline int skinny_ksplit(int dtype, int64_t M, int64_t N, int64_t K)
+{
+    if (!is16(dtype) || M <= 0) return 1;
+    const int64_t tiles = ((M + TILE - 1) / TILE) * ((N + TILE - 1) / TILE);
+    if (tiles * 2 > 256) return 1;
+    int64_t ks = 256 / tiles;
+    if (ks > 4) ks = 4;
+    if (ks > K / 1024) ks = K / 1024;
+    return ks < 1 ? 1 : (int)ks;
+}
+
 // ------------------------------------------------------------------------------------------------
 // one contraction, either dtype
 struct Seg { const void* a; int64_t lda; const void* b; int64_t ldb; int K; };
@@ -204,12 +219,24 @@ GemmArgs bf16_args(int dt, bool a_kc, bool b_kc, int M, int N, const Seg* segs, 
     return g;
 }
 
+// skp != nullptr (16-bit outputs, one segment): scratch for the K slices of a skinny product; the product is then
+// split as skinny_ksplit says.  c2 / alpha2: optional second output alpha2 * (A B^T) (16-bit storage only).
 hipError_t contract(int dtype, bool a_kc, bool b_kc, int M, int N, const Seg* segs, int nseg, float alpha, void* c,
-                    int64_t ldc, bool c_f32, int trace_id, hipStream_t st)
+                    int64_t ldc, bool c_f32, int trace_id, hipStream_t st, float* skp = nullptr, void* c2 = nullptr,
+                    float alpha2 = 0.f)
 {
     if (is16(dtype)) {
         const int tag = (trace_id == DORA_K_GEMM_LORA || trace_id == DORA_K_GEMM_DB) ? 1 : 0;
-        return launch_gemm_bf16(bf16_args(dt_of(dtype), a_kc, b_kc, M, N, segs, nseg, alpha, c, ldc, c_f32, tag), trace_id, st);
+        GemmArgs g = bf16_args(dt_of(dtype), a_kc, b_kc, M, N, segs, nseg, alpha, c, ldc, c_f32, tag);
+        const int ks = (skp && nseg == 1 && !c_f32 && ldc == N) ? skinny_ksplit(dtype, M, N, segs[0].K) : 1;
+        if (ks > 1) {
+            g.epilogue = EPI_STORE_F32; g.c = skp; g.ksplit = ks;
+            hipError_t e = launch_gemm_bf16(g, trace_id, st);
+            if (e != hipSuccess) return e;
+            return launch_splitk_reduce(skp, ks, (int64_t)M * N, dtype, c, alpha2, c2, st);
+        }
+        g.c2 = c2; g.alpha2 = alpha2;
+        return launch_gemm_bf16(g, trace_id, st);
     }
     SgemmArgs g;
     memset(&g, 0, sizeof(g));
@@ -296,6 +323,7 @@ struct FwdPlan {
     NormPlan norm;
     float *c, *g, *gm1;
     void *h, *lora, *hs, *base_a;
+    float* skp;   // K slices of the skinny product h = xa A^T (nullptr: not split)
 };
 void plan_fwd(const dora_desc* d, Bump& b, FwdPlan& p, bool need_norm, bool need_h, bool need_lora,
               bool need_hs = false, bool need_base_a = false)
@@ -309,12 +337,15 @@ void plan_fwd(const dora_desc* d, Bump& b, FwdPlan& p, bool need_norm, bool need
     if (need_lora) p.lora = b.take_bytes((size_t)d->tokens * d->d_out * esize(d->dtype));
     if (need_hs) p.hs = b.take_bytes((size_t)d->tokens * d->r * esize(d->dtype));
     if (need_base_a) p.base_a = b.take_bytes((size_t)d->tokens * d->d_out * esize(d->dtype));
+    const int ks = skinny_ksplit(d->dtype, d->tokens, d->r, d->d_in);
+    if (ks > 1) p.skp = b.take<float>((size_t)ks * d->tokens * d->r);
 }
 
 struct BwdPlan {
     NormPlan norm;
     float *c, *g, *gm1, *dm_partial;
     void *dz, *dh, *h, *inner, *dzb;
+    float* skp;   // K slices of the skinny products dh = s dz B and (recomputed) h = xa A^T
 };
 void plan_bwd(const dora_desc* d, Bump& b, BwdPlan& p, bool need_norm, bool need_h, bool need_inner,
               bool need_dzb = false)
@@ -330,6 +361,10 @@ void plan_bwd(const dora_desc* d, Bump& b, BwdPlan& p, bool need_norm, bool need
     if (need_h) p.h = b.take_bytes((size_t)d->tokens * d->r * esize(d->dtype));
     if (need_inner) p.inner = b.take_bytes((size_t)d->tokens * d->d_out * esize(d->dtype));
     if (need_dzb) p.dzb = b.take_bytes((size_t)d->tokens * d->d_out * esize(d->dtype));
+    const int ks_dh = skinny_ksplit(d->dtype, d->tokens, d->r, d->d_out);
+    const int ks_h = need_h ? skinny_ksplit(d->dtype, d->tokens, d->r, d->d_in) : 1;
+    const int ks = ks_dh > ks_h ? ks_dh : ks_h;
+    if (ks > 1) p.skp = b.take<float>((size_t)ks * d->tokens * d->r);
 }
 
 dora_status check_ws(void* ws, size_t ws_bytes, size_t need)
@@ -344,7 +379,8 @@ dora_status check_ws(void* ws, size_t ws_bytes, size_t need)
 // base = x W^T, h = x A^T, lora = h B^T (App. A item 1)
 // xa: the adapter branch's input (x itself unless LoRA dropout gives that branch an input of its own)
 dora_status forward_contractions(const dora_desc* d, const void* x, const void* W, const void* A, const void* B,
-                                 void* base, void* h, void* lora, hipStream_t st, const void* xa = nullptr)
+                                 void* base, void* h, void* lora, hipStream_t st, const void* xa = nullptr,
+                                 float* skp = nullptr)
 {
     const int T = (int)d->tokens, d_out = (int)d->d_out, d_in = (int)d->d_in, r = (int)d->r;
     Seg s0{x, d_in, W, d_in, d_in};
@@ -353,7 +389,7 @@ dora_status forward_contractions(const dora_desc* d, const void* x, const void* 
     // round behind the four full rounds of 256 x 256 base tiles and cost more than a launch of their own)
     // (h after base, not before: it then finds part of x still in the memory-side cache; the other order costs 10 us)
     DORA_HIP(contract(d->dtype, true, true, T, d_out, &s0, 1, 1.f, base, d_out, false, DORA_K_GEMM_BASE, st));
-    DORA_HIP(contract(d->dtype, true, true, T, r, &s1, 1, 1.f, h, r, false, DORA_K_GEMM_H, st));
+    DORA_HIP(contract(d->dtype, true, true, T, r, &s1, 1, 1.f, h, r, false, DORA_K_GEMM_H, st, skp));
     Seg s2{h, r, B, r, r};
     DORA_HIP(contract(d->dtype, true, true, T, d_out, &s2, 1, 1.f, lora, d_out, false, DORA_K_GEMM_LORA, st));
     return DORA_OK;
@@ -585,7 +621,7 @@ static dora_status forward_impl(const dora_desc* desc, const void* x, const void
     // base lands in y and lora in the inner buffer; the compose pass then runs in place on both
     void* h = saved_h ? saved_h : p.h;
     void* lora = saved_inner ? saved_inner : p.lora;
-    if ((st = forward_contractions(desc, x, W, A, B, y, h, lora, s, x_lora)) != DORA_OK) return st;
+    if ((st = forward_contractions(desc, x, W, A, B, y, h, lora, s, x_lora, p.skp)) != DORA_OK) return st;
     if (!dropout) {
         DORA_HIP(launch_compose_fwd(desc->dtype, y, lora, p.g, p.gm1, bias, desc->s, y, 0, saved_inner, T, d_out, s));
         return DORA_OK;
@@ -648,10 +684,7 @@ dora_status dora_forward_fused(const dora_desc* desc, const void* x, const void*
     // the low-rank operand of the K-concatenated product  [s h | x] [B | W]^T = s h B^T + x W^T
     void* h = saved_h ? saved_h : p.h;
     Seg s1{x, d_in, A, d_in, d_in};
-    GemmArgs gh = bf16_args(dt_of(desc->dtype), true, true, T, r, &s1, 1, 1.f, h, r, false, 0);
-    gh.c2 = p.hs;
-    gh.alpha2 = desc->s;
-    DORA_HIP(launch_gemm_bf16(gh, DORA_K_GEMM_H, s));
+    DORA_HIP(contract(desc->dtype, true, true, T, r, &s1, 1, 1.f, h, r, false, DORA_K_GEMM_H, s, p.skp, p.hs, desc->s));
     Seg segs[2] = {{p.hs, r, B, r, r}, {x, d_in, W, d_in, d_in}};
     GemmArgs g = bf16_args(dt_of(desc->dtype), true, true, T, d_out, segs, 2, 1.f, y, d_out, false, 0);
     g.epilogue = EPI_COMPOSE;
@@ -711,14 +744,14 @@ static dora_status backward_impl(const dora_desc* desc, const void* dy, const vo
             Seg s2{saved_h, r, B, r, r};
             DORA_HIP(contract(dt, true, true, T, d_out, &s2, 1, 1.f, p.inner, d_out, false, DORA_K_GEMM_LORA, s));
         } else {
-            if ((st = forward_contractions(desc, xa, W, A, B, p.dz, hbuf, p.inner, s)) != DORA_OK) return st;
+            if ((st = forward_contractions(desc, xa, W, A, B, p.dz, hbuf, p.inner, s, nullptr, p.skp)) != DORA_OK) return st;
             h = hbuf;
         }
         DORA_HIP(launch_compose_fwd(dt, p.dz, p.inner, p.g, p.gm1, nullptr, desc->s, nullptr, 0, p.inner, T, d_out, s));
         inner = p.inner;
     } else if (T > 0 && need_h) {
         Seg s1{xa, d_in, A, d_in, d_in};
-        DORA_HIP(contract(dt, true, true, T, r, &s1, 1, 1.f, p.h, r, false, DORA_K_GEMM_H, s));
+        DORA_HIP(contract(dt, true, true, T, r, &s1, 1, 1.f, p.h, r, false, DORA_K_GEMM_H, s, p.skp));
         h = p.h;
     }
 
@@ -731,7 +764,7 @@ static dora_status backward_impl(const dora_desc* desc, const void* dy, const vo
     // dh = s * dz B   (gradient reaching h)
     if ((dropout ? dx_lora : dx) || dA) {
         Seg sh{p.dz, d_out, B, r, d_out};
-        DORA_HIP(contract(dt, true, false, T, r, &sh, 1, desc->s, p.dh, r, false, DORA_K_GEMM_DH, s));
+        DORA_HIP(contract(dt, true, false, T, r, &sh, 1, desc->s, p.dh, r, false, DORA_K_GEMM_DH, s, p.skp));
     }
     if (!dropout) {
         if (dx) {  // dx = dz W + dh A : one contraction over the concatenated K range
@@ -837,7 +870,7 @@ const char* dora_trace_name(int kernel_id)
     static const char* names[DORA_K_COUNT] = {
         "norm_cross_WAt", "gram_AAt", "gram_reduce", "ba_sq_BGB", "norm_final", "mag_scale", "gemm_base_xWt",
         "gemm_h_xAt", "gemm_lora_hBt", "compose_fwd", "compose_bwd", "dm_final", "gemm_dh_dzB", "gemm_dx",
-        "gemm_dA", "gemm_dB", "probe_copy", "probe_mfma", "gemm_fused_fwd"};
+        "gemm_dA", "gemm_dB", "probe_copy", "probe_mfma", "gemm_fused_fwd", "splitk_reduce"};
     return (kernel_id >= 0 && kernel_id < DORA_K_COUNT) ? names[kernel_id] : "?";
 }
 

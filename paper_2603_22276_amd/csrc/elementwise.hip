@@ -131,6 +131,33 @@ __global__ void gram_reduce_kernel(const float* __restrict__ p, int ksplit, int 
     Glo[i] = (bf16_t)(E::pack2(rem, 0.f) & 0xffffu);
 }
 
+// Sum of the K slices of a split contraction, in slice order, rounded once to the storage dtype.
+template <typename T>
+__global__ void splitk_reduce_kernel(const float* __restrict__ p, int ksplit, int64_t n, T* __restrict__ out,
+                                     float alpha2, T* __restrict__ out2)
+{
+    typedef Vec<T> V;
+    constexpr int N = V::N;
+    const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * N;
+    if (i >= n) return;
+    float acc[N];
+#pragma unroll
+    for (int e = 0; e < N; ++e) acc[e] = 0.f;
+    for (int z = 0; z < ksplit; ++z) {
+#pragma unroll
+        for (int e = 0; e < N; e += 4) {
+            const float4 v = *reinterpret_cast<const float4*>(p + (int64_t)z * n + i + e);
+            acc[e] += v.x; acc[e + 1] += v.y; acc[e + 2] += v.z; acc[e + 3] += v.w;
+        }
+    }
+    *reinterpret_cast<typename V::raw_t*>(out + i) = V::pack(acc);
+    if (out2) {
+#pragma unroll
+        for (int e = 0; e < N; ++e) acc[e] *= alpha2;
+        *reinterpret_cast<typename V::raw_t*>(out2 + i) = V::pack(acc);
+    }
+}
+
 // fp32 configuration: the three terms of Eq. 2 for one row per wavefront, from U = W A^T and BG = B G.
 // base_in != nullptr: the base term is read from it instead of being summed from W (Sec. 2.3: W is frozen, so
 // its squared row norms can be computed once).  squared: write the radicand itself, not its root.
@@ -416,6 +443,22 @@ hipError_t launch_gram_reduce(const float* partials, int ksplit, int r, float* G
     TraceScope ts(DORA_K_GRAM_REDUCE, st);
     if (dt == DT_F16) gram_reduce_kernel<DT_F16><<<dim3((rr + 255) / 256), dim3(256), 0, st>>>(partials, ksplit, rr, G, Ghi, Glo);
     else gram_reduce_kernel<DT_BF16><<<dim3((rr + 255) / 256), dim3(256), 0, st>>>(partials, ksplit, rr, G, Ghi, Glo);
+    return hipGetLastError();
+}
+
+hipError_t launch_splitk_reduce(const float* partials, int ksplit, int64_t n, int dtype, void* out, float alpha2, void* out2,
+                                hipStream_t st)
+{
+    if (n == 0) return hipSuccess;
+    TraceScope ts(DORA_K_SPLITK_REDUCE, st);
+    const int per = dtype == DORA_F32 ? 4 : 8;
+    dim3 grid((unsigned)((n / per + 255) / 256)), block(256);
+    if (dtype == DORA_BF16)
+        splitk_reduce_kernel<bf16_t><<<grid, block, 0, st>>>(partials, ksplit, n, (bf16_t*)out, alpha2, (bf16_t*)out2);
+    else if (dtype == DORA_F16)
+        splitk_reduce_kernel<f16_t><<<grid, block, 0, st>>>(partials, ksplit, n, (f16_t*)out, alpha2, (f16_t*)out2);
+    else
+        splitk_reduce_kernel<float><<<grid, block, 0, st>>>(partials, ksplit, n, (float*)out, alpha2, (float*)out2);
     return hipGetLastError();
 }
 

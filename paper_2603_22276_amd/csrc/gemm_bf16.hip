@@ -807,6 +807,7 @@ hipError_t dispatch(const GemmArgs& a, const GemmArgs* b, hipStream_t stream)
     if (a.a_kcontig == (AKC) && a.b_kcontig == (BKC) && a.epilogue == (E))              \
         return DORA_GEMM_MED(AKC, BKC, E);
     DORA_GEMM_CASE_MED(true, true, EPI_STORE_F32)
+    DORA_GEMM_CASE_MED(true, false, EPI_STORE_F32)
     DORA_GEMM_CASE_MED(true, true, EPI_ROWDOT)
     DORA_GEMM_CASE_MED(false, false, EPI_STORE_F32)
 #undef DORA_GEMM_CASE_MED

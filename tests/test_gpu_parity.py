@@ -38,10 +38,14 @@ SMALL = [
     I.stress(cfg_bf16("bf16_mid", 1024, 1536, 384, 640, seed=4)),
     cfg_bf16("bf16_mid", 1024, 1536, 384, 640, seed=4),
     cfg_bf16("bf16_bigtile_ragged", 4104, 264, 16, 4104, sigma_B=2e-2, seed=5),
+    # few tiles and a long K: h = x A^T (first) and dh = s dz B (second) run split along K with a fixed-order reduce
+    cfg_bf16("bf16_splitk_h", 264, 2312, 40, 300, seed=8),
+    cfg_bf16("bf16_splitk_dh", 3080, 264, 24, 200, sigma_B=2e-2, seed=9),
     # fp16 storage (App. B): the same kernels with the fp16 MFMA and conversions
     cfg_f16("f16_ragged_tiny", 200, 328, 24, 77, seed=2),
     I.stress(cfg_f16("f16_mid", 1024, 1536, 384, 640, seed=4)),
     cfg_f16("f16_bigtile_ragged", 4104, 264, 16, 4104, sigma_B=2e-2, seed=5),
+    cfg_f16("f16_splitk_h", 264, 2312, 40, 300, seed=8),
 ]
 IDS = [c.name for c in SMALL]
 
@@ -530,7 +534,7 @@ def test_fused_forward_rejects_fp32():
 
 # ----------------------------------------------------------------------------- LoRA dropout (App. B)
 
-DROPOUT_CASES = [SMALL[1], SMALL[3], SMALL[4], SMALL[7]]
+DROPOUT_CASES = [SMALL[1], SMALL[3], SMALL[4], SMALL[7], SMALL[9]]
 
 
 @pytest.mark.parametrize("cfg", DROPOUT_CASES, ids=[c.name for c in DROPOUT_CASES])
@@ -589,7 +593,7 @@ def test_dropout_entry_points_without_dropout_are_the_plain_module():
 
 # ----------------------------------------------------------------------------- bias of the base layer
 
-@pytest.mark.parametrize("cfg", [SMALL[0], SMALL[2], SMALL[5], SMALL[6], SMALL[8]], ids=[IDS[0], IDS[2], IDS[5], IDS[6], IDS[8]])
+@pytest.mark.parametrize("cfg", [SMALL[0], SMALL[2], SMALL[5], SMALL[6], SMALL[10]], ids=[IDS[0], IDS[2], IDS[5], IDS[6], IDS[10]])
 @pytest.mark.parametrize("fused", [False, True], ids=["compose_pass", "fused_epilogue"])
 def test_forward_with_bias(cfg, fused):
     # App. A item 2: the frozen layer's bias is not part of the compose; y = base + delta + bias
