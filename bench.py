@@ -249,6 +249,8 @@ def kernel_table(D, torch, wl, reps, dominant_live):
         # launches that carry two contractions at once are priced with the work of both
         if got["gemm_dA"][1] > 0 and got["gemm_dB"][1] == 0:
             w["gemm_dA"] = (w["gemm_dA"][0] + w["gemm_dB"][0], w["gemm_dA"][1] + w["gemm_dB"][1])
+        if got["norm_cross_WAt"][1] > 0 and got["gram_AAt"][1] == 0:   # the Gram tiles ride in the cross term's launch
+            w["norm_cross_WAt"] = (w["norm_cross_WAt"][0] + w["gram_AAt"][0], w["norm_cross_WAt"][1] + w["gram_AAt"][1])
         for n, (_, cnt) in got.items():
             if cnt and n in w:
                 tot[n]["flops"] += w[n][0] * cnt

@@ -88,8 +88,8 @@ dora_status dora_norm(const dora_desc* desc, const void* W, const void* A, const
  * hipFree or other allocating routine.
  *   - The array is dora_norm_static_max_bytes() = 16 MiB of device memory per GPU the library runs
  *     on, held until the process ends.  A shape whose dora_workspace_bytes(desc, DORA_PHASE_NORM)
- *     exceeds it is rejected with DORA_ERR_WORKSPACE before anything is enqueued (all five workload
- *     shapes at r <= 512 fit; r = 768 does not).
+ *     exceeds it is rejected with DORA_ERR_WORKSPACE before anything is enqueued (the workload
+ *     shapes fit at every rank up to 768; r = 2048 at d_out = 8192 does not).
  *   - All calls on one GPU share that one array: two calls that overlap in time on the same GPU (two
  *     streams, two threads) race.  Calls ordered on one stream are safe; nothing needs clearing between
  *     them because each launch overwrites in full what the next one reads.

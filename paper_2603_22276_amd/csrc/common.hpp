@@ -173,8 +173,10 @@ hipError_t launch_dm_final(const float* partial, int slabs, const float* c, floa
 hipError_t launch_gram_reduce(const float* partials, int ksplit, int r, float* G, bf16_t* Ghi, bf16_t* Glo, int dt,
                               hipStream_t st);
 // c and / or terms ([3, d_out]: the summed base_sq, cross, ba_sq) may be nullptr
+// m != nullptr: Eq. 6 in the same launch (g and / or gm1 from m, the norm just formed and eps)
 hipError_t launch_norm_final(const float* base_sq_p, int n_base, const float* cross_p, int n_cross, const float* ba_p,
-                             int n_ba, double s, float* c, float* terms, int d_out, hipStream_t st);
+                             int n_ba, double s, float* c, float* terms, int d_out, hipStream_t st,
+                             const float* m = nullptr, float eps = 0.f, float* g = nullptr, float* gm1 = nullptr);
 hipError_t launch_rownorm_s0_16(const bf16_t* W, int dt, float* c, int d_out, int d_in, bool squared, hipStream_t st);
 // fp32 path: base_sq, cross, ba_sq and Eq. 5 from W, B, U = W A^T, BG = B G (all fp32)
 hipError_t launch_rownorm_f32(const float* W, const float* base_in, const float* B, const float* U, const float* BG,

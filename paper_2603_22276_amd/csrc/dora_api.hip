@@ -168,8 +168,10 @@ void plan_norm(const dora_desc* d, Bump& b, NormPlan& n)
     if (n.ks_u > 8) n.ks_u = 8;
     if (n.ks_u > ktiles) n.ks_u = ktiles;
     if (n.ks_u < 1) n.ks_u = 1;
+    // the Gram workgroups ride in the cross term's launch: give them what that leaves of the round
     const int tiles_g = n.tiles_n * n.tiles_n;
-    n.ks_g = 512 / tiles_g;
+    const int left = 512 - tiles_u * n.ks_u;
+    n.ks_g = (left > 0 ? left : 512) / tiles_g;
     if (n.ks_g > 16) n.ks_g = 16;
     if (n.ks_g > ktiles) n.ks_g = ktiles;
     if (n.ks_g < 1) n.ks_g = 1;
@@ -255,8 +257,12 @@ hipError_t contract(int dtype, bool a_kc, bool b_kc, int M, int N, const Seg* se
 // base_sq != nullptr: the base term of Eq. 2 comes from the caller's cache and W is not squared again
 // c == nullptr: only the terms are wanted.  terms != nullptr: [3, d_out] fp32 receives base_sq, cross, ba_sq.
 // G_out != nullptr: [r, r] fp32 receives the Gram matrix of Eq. 4.
+// Eq. 6 riding on the norm's last launch: set `done` when g / gm1 were written there
+struct MagOut { const float* m; float eps; float* g; float* gm1; bool done; };
+
 dora_status norm_impl(const dora_desc* d, const void* W, const void* A, const void* B, float* c, const NormPlan& n,
-                      hipStream_t st, const float* base_sq = nullptr, float* terms = nullptr, float* G_out = nullptr)
+                      hipStream_t st, const float* base_sq = nullptr, float* terms = nullptr, float* G_out = nullptr,
+                      MagOut* mag = nullptr)
 {
     const int d_out = (int)d->d_out, d_in = (int)d->d_in, r = (int)d->r;
     if (d->s == 0.f) {  // scale-is-zero fast path: no U, no G
@@ -284,13 +290,14 @@ dora_status norm_impl(const dora_desc* d, const void* W, const void* A, const vo
         g.nseg = 1; g.M = d_out; g.N = r; g.a_kcontig = 1; g.b_kcontig = 1; g.epilogue = EPI_ROWDOT; g.alpha = 1.f; g.dt = dt;
         g.ksplit = n.ks_u; g.rowdot = (const bf16_t*)B; g.ld_rowdot = r; g.rowdot_partial = n.cross_p;
         g.base_sq_partial = base_sq ? nullptr : n.base_p;
-        DORA_HIP(launch_gemm_bf16(g, DORA_K_NORM_CROSS, st));
-        // Gram matrix (Eq. 4): split-K partials, then a fixed-order sum and the hi/lo bf16 expansion
-        memset(&g, 0, sizeof(g));
-        g.seg[0] = GemmSeg{(const bf16_t*)A, (const bf16_t*)A, d_in, d_in, d_in};
-        g.nseg = 1; g.M = r; g.N = r; g.a_kcontig = 1; g.b_kcontig = 1; g.epilogue = EPI_STORE_F32; g.alpha = 1.f; g.dt = dt;
-        g.c = n.gram_p; g.ldc = r; g.ksplit = n.ks_g;
-        DORA_HIP(launch_gemm_bf16(g, DORA_K_GRAM, st));
+        // Gram matrix (Eq. 4): split-K partials, then a fixed-order sum and the hi/lo 16-bit expansion.  It is
+        // independent of the cross term and far too small to fill the chip, so its workgroups ride in the same launch.
+        GemmArgs gg;
+        memset(&gg, 0, sizeof(gg));
+        gg.seg[0] = GemmSeg{(const bf16_t*)A, (const bf16_t*)A, d_in, d_in, d_in};
+        gg.nseg = 1; gg.M = r; gg.N = r; gg.a_kcontig = 1; gg.b_kcontig = 1; gg.epilogue = EPI_STORE_F32; gg.alpha = 1.f;
+        gg.dt = dt; gg.c = n.gram_p; gg.ldc = r; gg.ksplit = n.ks_g;
+        DORA_HIP(launch_gemm_bf16_pair(g, gg, DORA_K_NORM_CROSS, st));
         DORA_HIP(launch_gram_reduce(n.gram_p, n.ks_g, r, G_out, n.Ghi, n.Glo, dt, st));
         // BA-norm term: rowdot(B, B G) with G = Ghi + Glo kept to ~16 mantissa bits (G is symmetric,
         // so G serves as its own K-contiguous N-side operand)
@@ -301,7 +308,9 @@ dora_status norm_impl(const dora_desc* d, const void* W, const void* A, const vo
         g.ksplit = 1; g.rowdot = (const bf16_t*)B; g.ld_rowdot = r; g.rowdot_partial = n.ba_p; g.tag = 1;
         DORA_HIP(launch_gemm_bf16(g, DORA_K_BA_SQ, st));
         DORA_HIP(launch_norm_final(base_sq ? base_sq : n.base_p, base_sq ? 1 : n.ks_u, n.cross_p, n.ks_u * n.tiles_n,
-                                   n.ba_p, n.tiles_n, (double)d->s, c, terms, d_out, st));
+                                   n.ba_p, n.tiles_n, (double)d->s, c, terms, d_out, st, mag ? mag->m : nullptr,
+                                   mag ? mag->eps : 0.f, mag ? mag->g : nullptr, mag ? mag->gm1 : nullptr));
+        if (mag) mag->done = true;
         return DORA_OK;
     }
     // fp32: Algorithm 1 with one chunk spanning d_in; U [d_out, r], G [r, r], BG [d_out, r] in scratch
@@ -608,16 +617,17 @@ static dora_status forward_impl(const dora_desc* desc, const void* x, const void
     hipStream_t s = (hipStream_t)stream;
     const int T = (int)desc->tokens, d_out = (int)desc->d_out, d_in = (int)desc->d_in;
 
+    MagOut mag{m, eff_eps(desc), p.g, p.gm1, false};
     const float* c = w_norm;
     if (need_norm) {
         float* cw = w_norm_out ? w_norm_out : p.c;
-        if ((st = norm_impl(desc, W, A, B, cw, p.norm, s)) != DORA_OK) return st;
+        if ((st = norm_impl(desc, W, A, B, cw, p.norm, s, nullptr, nullptr, nullptr, &mag)) != DORA_OK) return st;
         c = cw;
     } else if (w_norm_out && w_norm_out != w_norm) {
         DORA_HIP(hipMemcpyAsync(w_norm_out, w_norm, sizeof(float) * d_out, hipMemcpyDeviceToDevice, s));
     }
     if (T == 0) return DORA_OK;
-    DORA_HIP(launch_mag_scale(m, c, eff_eps(desc), p.g, p.gm1, d_out, s));
+    if (!mag.done) DORA_HIP(launch_mag_scale(m, c, eff_eps(desc), p.g, p.gm1, d_out, s));
     // base lands in y and lora in the inner buffer; the compose pass then runs in place on both
     void* h = saved_h ? saved_h : p.h;
     void* lora = saved_inner ? saved_inner : p.lora;
@@ -670,16 +680,17 @@ dora_status dora_forward_fused(const dora_desc* desc, const void* x, const void*
     hipStream_t s = (hipStream_t)stream;
     const int T = (int)desc->tokens, d_out = (int)desc->d_out, d_in = (int)desc->d_in, r = (int)desc->r;
 
+    MagOut mag{m, eff_eps(desc), p.g, nullptr, false};
     const float* c = w_norm;
     if (need_norm) {
         float* cw = w_norm_out ? w_norm_out : p.c;
-        if ((st = norm_impl(desc, W, A, B, cw, p.norm, s)) != DORA_OK) return st;
+        if ((st = norm_impl(desc, W, A, B, cw, p.norm, s, nullptr, nullptr, nullptr, &mag)) != DORA_OK) return st;
         c = cw;
     } else if (w_norm_out && w_norm_out != w_norm) {
         DORA_HIP(hipMemcpyAsync(w_norm_out, w_norm, sizeof(float) * d_out, hipMemcpyDeviceToDevice, s));
     }
     if (T == 0) return DORA_OK;
-    DORA_HIP(launch_mag_scale(m, c, eff_eps(desc), p.g, nullptr, d_out, s));
+    if (!mag.done) DORA_HIP(launch_mag_scale(m, c, eff_eps(desc), p.g, nullptr, d_out, s));
     // h = x A^T, written twice from the same accumulators: as it is (the saved tensor) and scaled by s,
     // the low-rank operand of the K-concatenated product  [s h | x] [B | W]^T = s h B^T + x W^T
     void* h = saved_h ? saved_h : p.h;
@@ -725,12 +736,13 @@ static dora_status backward_impl(const dora_desc* desc, const void* dy, const vo
     const int T = (int)desc->tokens, d_out = (int)desc->d_out, d_in = (int)desc->d_in, r = (int)desc->r;
     const int dt = desc->dtype;
 
+    MagOut mag{m, eff_eps(desc), p.g, p.gm1, false};
     const float* c = w_norm;
     if (need_norm) {
-        if ((st = norm_impl(desc, W, A, B, p.c, p.norm, s)) != DORA_OK) return st;
+        if ((st = norm_impl(desc, W, A, B, p.c, p.norm, s, nullptr, nullptr, nullptr, &mag)) != DORA_OK) return st;
         c = p.c;
     }
-    DORA_HIP(launch_mag_scale(m, c, eff_eps(desc), p.g, p.gm1, d_out, s));
+    if (!mag.done) DORA_HIP(launch_mag_scale(m, c, eff_eps(desc), p.g, p.gm1, d_out, s));
 
     const void* h = saved_h;
     const void* inner = saved_inner;

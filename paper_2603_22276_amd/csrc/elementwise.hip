@@ -91,10 +91,12 @@ __global__ void mag_scale_kernel(const float* __restrict__ m, const float* __res
 
 // Eq. 5 from the partial sums the norm kernels left behind; partials are added in index order.
 // terms != nullptr: the three summed terms are also written, as rows of a [3, d_out] array (base_sq,
-// cross, ba_sq); c == nullptr: only the terms are wanted.
+// cross, ba_sq); c == nullptr: only the terms are wanted.  m != nullptr: Eq. 6 follows in the same launch
+// (g and / or gm1, exactly as mag_scale_kernel forms them).
 __global__ void norm_final_kernel(const float* __restrict__ base_p, int n_base, const float* __restrict__ cross_p,
                                   int n_cross, const float* __restrict__ ba_p, int n_ba, float two_s, float s2,
-                                  float* __restrict__ c, float* __restrict__ terms, int d_out)
+                                  float* __restrict__ c, float* __restrict__ terms, int d_out,
+                                  const float* __restrict__ m, float eps, float* __restrict__ g, float* __restrict__ gm1)
 {
     int j = blockIdx.x * blockDim.x + threadIdx.x;
     if (j >= d_out) return;
@@ -110,7 +112,14 @@ __global__ void norm_final_kernel(const float* __restrict__ base_p, int n_base, 
     if (!c) return;
     float rad = base_sq + two_s * cross + s2 * ba;
     rad = (rad < 0.f) ? 0.f : rad;  // NaN is not < 0: it propagates (App. C item 3)
-    c[j] = __fsqrt_rn(rad);
+    const float cj = __fsqrt_rn(rad);
+    c[j] = cj;
+    if (m) {
+        float cc = (cj < eps) ? eps : cj;
+        float mj = m[j];
+        if (g) g[j] = mj / cc;
+        if (gm1) gm1[j] = (mj - cc) / cc;
+    }
 }
 
 // G = sum of split-K partials (fixed order), and its two-term 16-bit expansion G ~ Ghi + Glo.
@@ -425,13 +434,15 @@ hipError_t launch_mag_scale(const float* m, const float* c, float eps, float* g,
 }
 
 hipError_t launch_norm_final(const float* base_p, int n_base, const float* cross_p, int n_cross, const float* ba_p,
-                             int n_ba, double s, float* c, float* terms, int d_out, hipStream_t st)
+                             int n_ba, double s, float* c, float* terms, int d_out, hipStream_t st, const float* m,
+                             float eps, float* g, float* gm1)
 {
     if (d_out == 0) return hipSuccess;
     TraceScope ts(DORA_K_NORM_FINAL, st);
     // 2s and s^2 are formed in double and rounded once (App. C item 3)
     norm_final_kernel<<<dim3((d_out + 255) / 256), dim3(256), 0, st>>>(base_p, n_base, cross_p, n_cross, ba_p, n_ba,
-                                                                       (float)(2.0 * s), (float)(s * s), c, terms, d_out);
+                                                                       (float)(2.0 * s), (float)(s * s), c, terms, d_out,
+                                                                       m, eps, g, gm1);
     return hipGetLastError();
 }
 

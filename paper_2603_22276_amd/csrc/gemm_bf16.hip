@@ -652,7 +652,9 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
     __syncthreads();
 
     // ------------------------------------------------------------------------------ epilogues
-    if (EPI == EPI_ROWDOT) {
+    // (a row-dot instance may carry a second problem that stores its fp32 tile instead: the Gram matrix riding
+    // along with the cross term; it falls through to the store epilogue below)
+    if (EPI == EPI_ROWDOT && p.epilogue == EPI_ROWDOT) {
         float* red = reinterpret_cast<float*>(smem);          // [WGN][BM] row-dot, then [WGN][BM] base_sq
         float* red2 = red + T::WGN * BM;
 #pragma unroll
@@ -828,9 +830,11 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, int trace_id, hipStream_t stream)
 
 hipError_t launch_gemm_bf16_pair(const GemmArgs& a, const GemmArgs& b, int trace_id, hipStream_t stream)
 {
-    // both problems run the same kernel instance: same operand layouts, epilogue, no split-K
-    if (a.a_kcontig != b.a_kcontig || a.b_kcontig != b.b_kcontig || a.epilogue != b.epilogue || a.ksplit != 1 ||
-        b.ksplit != 1)
+    // both problems run the same kernel instance: same operand layouts and element type; same epilogue without
+    // split-K, or a row-dot problem (split or not) followed by an fp32-store problem (split or not)
+    const bool same = a.epilogue == b.epilogue && a.ksplit == 1 && b.ksplit == 1;
+    const bool rowdot_then_store = a.epilogue == EPI_ROWDOT && b.epilogue == EPI_STORE_F32 && b.nseg == 1;
+    if (a.a_kcontig != b.a_kcontig || a.b_kcontig != b.b_kcontig || a.dt != b.dt || !(same || rowdot_then_store))
         return hipErrorInvalidValue;
     if ((a.M == 0 || a.N == 0) && (b.M == 0 || b.N == 0)) return hipSuccess;
     TraceScope ts(trace_id, stream);

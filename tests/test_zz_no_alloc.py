@@ -43,7 +43,7 @@ def test_static_scratch_norm_matches_workspace_norm_twice_in_a_row():
 
 
 def test_static_scratch_rejects_shapes_beyond_its_size():
-    d = D.make_desc(8192, 8192, 768, 0, D.DORA_BF16, 1.0)
+    d = D.make_desc(8192, 8192, 2048, 0, D.DORA_BF16, 1.0)
     assert D.dora_workspace_bytes(d, D.PHASE_NORM) > D.dora_norm_static_max_bytes()
     fake = 0x10000
     with pytest.raises(D.DoraError) as e:
