@@ -26,15 +26,19 @@
 #include <type_traits>
 #include <utility>
 
+#ifndef DORA_RS
+#define DORA_RS 2
+#endif
 namespace dora {
 namespace {
 
 constexpr int NUM_XCD = 8;
 constexpr int GROUP_M = 8;
 
-template <int BM_, int BN_, int WGM_, int WGN_, int BK_, int STAGES_>
+template <int BM_, int BN_, int WGM_, int WGN_, int BK_, int STAGES_, bool MI16_ = false>
 struct Tile {
     static constexpr int BM = BM_, BN = BN_, WGM = WGM_, WGN = WGN_;
+    static constexpr bool MI16 = MI16_;     // 16x16x32 MFMAs (8 x 8 per wave) instead of 32x32x16 (4 x 4)
     static constexpr int BK = BK_;          // K step per LDS buffer (elements)
     static constexpr int CPR = BK / 8;      // 16-byte chunks per K-contiguous LDS row
     static constexpr int STAGES = STAGES_;  // LDS ring depth (K steps)
@@ -58,10 +62,11 @@ struct Tile {
     static_assert(BK == 64, "the LDS layouts are written for K steps of 64");
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
     static_assert(WAVES == 4, "the schedules are written for four waves");
+    static_assert(!MI16 || (SPLIT_RING && WM == 128 && WN == 128), "the 16x16x32 schedule is written for 128 x 128 per wave");
     static_assert((BM * CPR) % THREADS == 0 && (BN * CPR) % THREADS == 0, "load plan must divide evenly");
 };
 
-typedef Tile<256, 256, 2, 2, 64, 2> TileBig;      // 256 threads, (3 + 2) x 32 KB of LDS, 256 accumulator registers (AGPRs) per lane
+typedef Tile<256, 256, 2, 2, 64, 2, true> TileBig; // 256 threads, (3 + 2) x 32 KB of LDS, 256 accumulator registers (AGPRs) per lane
 typedef Tile<128, 128, 2, 2, 64, 2> TileMed;      // 256 threads, 2 x 32 KB of LDS, two workgroups fit a CU
 typedef Tile<128, 128, 2, 2, 64, 4> TileMedDeep;  // the same with a ring of four, for launches of at most one workgroup per CU
 
@@ -88,12 +93,17 @@ __device__ __forceinline__ int lds_off(int row, int k)
     return row * (BK * 2) + ((((k >> 3) ^ kc_swizzle<BK>(row)) & (BK / 8 - 1)) << 4) + ((k & 7) << 1);
 }
 // K-strided operand: kept as loaded, [BK][ROWS] bf16; chunks of 8 rows XORed with 4*(k mod 4) so the four
-// k-rows one transposing read touches fall into different slots.
+// k-rows one transposing read touches fall into different slots, and with 2*(bit 3 of k) so that two
+// 16-lane blocks reading the same rows 8 k-rows apart do too.
+__device__ __forceinline__ int ks_swizzle(int k)
+{
+    return ((k & 3) << 2) | (((k >> 3) & 1) << 1);
+}
 template <int ROWS>
 __device__ __forceinline__ int lds_off_ks(int row, int k)
 {
     static_assert(ROWS >= 128, "swizzle needs at least 16 chunks per k-row");
-    return k * (ROWS * 2) + ((((row >> 3) ^ ((k & 3) << 2))) << 4) + ((row & 7) << 1);
+    return k * (ROWS * 2) + ((((row >> 3) ^ ks_swizzle(k))) << 4) + ((row & 7) << 1);
 }
 
 // Compile-time loop: f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N - 1>{})
@@ -146,6 +156,15 @@ __device__ __forceinline__ uint32_t frag_off(int row0, int k16, int lane)
                                       k16 * 16 + (lane >> 5) * 8 + ((lane & 15) >> 2));
 }
 
+// The same for the 16x16x32 MFMA: the lane gets row row0 + (lane & 15), k = k32*32 + 8*(lane >> 4) + 0..7.
+// K-strided tile: the lane points at k-row k32*32 + 8*(lane >> 4) + (lane & 15) / 4 and rows 4*(lane & 3) .. +3.
+template <int ROWS, int BK, bool KCONTIG>
+__device__ __forceinline__ uint32_t frag16_off(int row0, int k32, int lane)
+{
+    if (KCONTIG) return (uint32_t)lds_off<BK>(row0 + (lane & 15), k32 * 32 + (lane >> 4) * 8);
+    return (uint32_t)lds_off_ks<ROWS>(row0 + (lane & 3) * 4, k32 * 32 + (lane >> 4) * 8 + ((lane & 15) >> 2));
+}
+
 // Global -> LDS for one [ROWS x BK] operand tile.  Each wave-wide load instruction fills 1 KB of
 // contiguous LDS (lane i lands at byte 16*i of it), so lane i fetches from global memory whatever
 // belongs at that position of the swizzled tile; consecutive lanes cover one row segment of 2*BK bytes.
@@ -170,7 +189,7 @@ struct OperandLoader {
             k = (((pos % CPR) ^ kc_swizzle<BK>(row)) & (CPR - 1)) * 8;
         } else {
             k = pos / (ROWS / 8);
-            row = ((pos % (ROWS / 8)) ^ ((k & 3) << 2)) * 8;
+            row = ((pos % (ROWS / 8)) ^ ks_swizzle(k)) * 8;
         }
     }
     // The k index (inside the K step) of load i is that of load 0 plus a compile-time increment: zero for
@@ -221,8 +240,7 @@ struct Cursor {
     __amdgpu_buffer_rsrc_t rs;
     uint32_t so, so_step;   // scalar byte offset of the next K step and its increment
     int krem;               // k still to load in the segment (<= 0: exhausted, every further load brings zeros)
-    int seg;
-    __device__ __forceinline__ void open(int sidx, const bf16_t* base, int64_t ld, int K, int row0, int rows, int k_first,
+    __device__ __forceinline__ void open(const bf16_t* base, int64_t ld, int K, int row0, int rows, int k_first,
                                          int k_last, int wave, int lane)
     {
         rs = L::make_rsrc(base, ld, rows, K);
@@ -230,7 +248,6 @@ struct Cursor {
         so_step = KCONTIG ? (uint32_t)(BK * 2) : (uint32_t)(BK * ld * 2);
         so = KCONTIG ? (uint32_t)(k_first * 2) : (uint32_t)((int64_t)k_first * ld * 2);
         krem = (k_last < K ? k_last : K) - k_first;
-        seg = sidx;
     }
     template <int I>
     __device__ __forceinline__ void issue_one(char* tile, int wave) const
@@ -323,13 +340,25 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
     }
     const int nsteps = t_end - t_begin;
 
-    f32x16_t acc[MT][NT];
+    constexpr bool MI16 = T::MI16;
+    constexpr int M16 = MI16 ? T::WM / 16 : 1, N16 = MI16 ? T::WN / 16 : 1;  // 16 x 16 accumulator tiles per wave
+    f32x16_t acc[MI16 ? 1 : MT][MI16 ? 1 : NT];
+    f32x4_t acc16[M16][N16];
+    if constexpr (MI16) {
 #pragma unroll
-    for (int i = 0; i < MT; ++i)
+        for (int i = 0; i < M16; ++i)
 #pragma unroll
-        for (int j = 0; j < NT; ++j)
+            for (int j = 0; j < N16; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+                for (int e = 0; e < 4; ++e) acc16[i][j][e] = 0.f;
+    } else {
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    }
     float bsq[MT];
 #pragma unroll
     for (int i = 0; i < MT; ++i) bsq[i] = 0.f;
@@ -344,22 +373,26 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
     const int seg0_k0 = t_begin * BK, seg0_k1 = (t_end < kt0_total ? t_end : kt0_total) * BK;
     auto open_a = [&](int sidx) {
         const GemmSeg& sg = p.seg[sidx];
-        ca.open(sidx, sg.a, sg.lda, sg.K, m0, p.M, sidx ? 0 : seg0_k0, sidx ? sg.K : seg0_k1, wave, lane);
+        ca.open(sg.a, sg.lda, sg.K, m0, p.M, sidx ? 0 : seg0_k0, sidx ? sg.K : seg0_k1, wave, lane);
     };
     auto open_b = [&](int sidx) {
         const GemmSeg& sg = p.seg[sidx];
-        cb.open(sidx, sg.b, sg.ldb, sg.K, n0, p.N, sidx ? 0 : seg0_k0, sidx ? sg.K : seg0_k1, wave, lane);
+        cb.open(sg.b, sg.ldb, sg.K, n0, p.N, sidx ? 0 : seg0_k0, sidx ? sg.K : seg0_k1, wave, lane);
     };
     open_a(0);
     open_b(0);
-    if (ca.krem <= 0 && has_seg1) { open_a(1); open_b(1); }
+    // K steps each cursor still has to issue before it moves on to segment 1 (counts down; never reaches
+    // zero again once it is negative)
+    const int seg0_steps = (t_end < kt0_total ? t_end : kt0_total) - t_begin;
+    int a_left = (has_seg1 && seg0_steps > 0) ? seg0_steps : -1, b_left = a_left;
+    if (has_seg1 && seg0_steps <= 0) { open_a(1); open_b(1); }
     auto advance_a = [&]() {
         ca.step();
-        if (ca.krem <= 0 && ca.seg == 0 && has_seg1) open_a(1);
+        if (--a_left == 0) open_a(1);
     };
     auto advance_b = [&]() {
         cb.step();
-        if (cb.krem <= 0 && cb.seg == 0 && has_seg1) open_b(1);
+        if (--b_left == 0) open_b(1);
     };
     auto issue = [&](int slot) {   // every load of the next K step of both operands
         ca.issue_all(smem + T::a_slot_off(slot), wave);
@@ -424,101 +457,116 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
         }
     };
     auto mma = [&](const bf16x8_t (&af)[MT], const bf16x8_t (&bfr)[NT], int kk) {
+        if constexpr (!MI16) {
 #pragma unroll
-        for (int i = 0; i < MT; ++i)
+            for (int i = 0; i < MT; ++i)
 #pragma unroll
-            for (int j = 0; j < NT; ++j)
-                acc[i][j] = E::mfma(bfr[j], af[i], acc[i][j]);
-        base_term(af, kk);
+                for (int j = 0; j < NT; ++j)
+                    acc[i][j] = E::mfma(bfr[j], af[i], acc[i][j]);
+            base_term(af, kk);
+        }
     };
 
     bf16x8_t a0[MT], b0[NT], a1[MT], b1[NT];
-    if constexpr (T::SPLIT_RING) {
-        // Four waves, one per SIMD, each owning 128 x 128 of the tile (accumulators in the AGPR half of
-        // the register file).  This shape needs the fewest LDS bytes per MFMA (eight fragment reads feed
-        // sixteen MFMAs), which matters because the LDS path of a SIMD moves a 16-byte-per-lane read in
-        // about the time of one MFMA.  With a single wave per SIMD nothing else hides the issue of memory
-        // instructions, so they are interleaved with the MFMAs by hand.  A "burst" runs the sixteen
-        // MFMAs of one k-step from one fragment set; behind each of the first eight, one fragment of the
-        // next k-step is read into the other set; behind the others, a quarter of a K step's global
-        // loads is issued.  (All of a K step's loads behind one barrier would block the waves at the
-        // address unit, which takes 16 cycles per load instruction.)  One workgroup barrier per K step.
+    if constexpr (MI16) {
+        // Four waves, one per SIMD, each owning 128 x 128 of the tile as 8 x 8 accumulator tiles of
+        // v_mfma_f32_16x16x32 (accumulators in the AGPR half of the register file).  At the power limit the
+        // chip sustains about a tenth more flops with this instruction than with 32x32x16 (register-resident
+        // loops on random operands: 0.78 against 0.70 of the 2.4 GHz peak): it reads and writes the
+        // accumulators half as often per flop.  The LDS traffic is the same: sixteen fragment reads (eight
+        // per operand) feed the 64 MFMAs of a k-step of 32.  128 x 128 per wave needs the fewest LDS bytes
+        // per MFMA, and with a single wave per SIMD nothing else hides the issue of memory instructions, so
+        // they are interleaved with the MFMAs by hand; a 16-cycle MFMA leaves room for three other
+        // instructions of the same wave, so whatever can be is kept out of the loop (addresses in immediates).
         //
-        // LDS holds three M-side tiles and two N-side tiles.  With barrier(u) = the barrier at which all
-        // reads of K step u are done, the loads of a step are issued as
-        //     N side, step u+2:  first half behind barrier(u), second half in the burst after it,
-        //     M side, step u+3:  the two bursts after that,
-        // N side before M side, so that waiting for all but the last M-side step's loads means the N-side
-        // ones have landed (loads complete in order).  The N-side loads have about one K step to land (they
-        // are needed at barrier(u+1)), the M-side ones about one and a half (barrier(u+2)); with two slots
-        // for both operands every load of a step would have to be issued and to land within one step.
-        constexpr int NM = MT * NT, NF = MT + NT;
-        constexpr int HA = T::NLA / 2, HB = T::NLB / 2;
-        static_assert(KSTEPS == 4 && NF <= NM && STAGES == 2, "burst schedule assumptions");
-        // MFMAs of the k-step held in (xa, xb); fragments of k-step KK of (sa, sb) -> (na, nb); loads
-        // [D0, D0 + DN) of the M side (SIDE 0) or N side (SIDE 1) into `tile`
-        auto burst = [&](auto kk_tag, auto side_tag, auto d0_tag, auto dn_tag, const bf16x8_t (&xa)[MT],
-                         const bf16x8_t (&xb)[NT], bf16x8_t (&na)[MT], bf16x8_t (&nb)[NT], uint32_t sa, uint32_t sb,
-                         char* tile) {
-            constexpr int SIDE = decltype(side_tag)::value, D0 = decltype(d0_tag)::value, DN = decltype(dn_tag)::value;
+        // A "burst" runs the 64 MFMAs of one k-step from one fragment set; behind each of the first sixteen,
+        // one fragment of the next k-step is read into the other set, in the order the next burst needs
+        // them; behind the others, one operand's eight global loads of a K step are issued, one every sixth
+        // MFMA.  A K step is two bursts with the workgroup barrier between them.
+        //
+        // LDS holds three M-side tiles and two N-side tiles.  With barrier(u) = the barrier in the middle of
+        // K step u, at which every wave's fragment reads of step u are done:
+        //     burst before barrier(u):  M side of step u+2 -> the slot step u-1 used (free since barrier(u-1))
+        //     burst after barrier(u):   N side of step u+2 -> the slot step u used; fragments of step u+1
+        // At barrier(u) everything but the M side of step u+2 has landed (loads complete in order), which
+        // includes all of step u+1.  Either side has about one K step to land.
+        //
+        // The loop takes two K steps per trip, so that the N-side slot, and with it every N-side LDS address,
+        // is a compile-time offset.  An odd number of K steps is rounded up: the loads past the end of the
+        // schedule bring zeros, so the extra step adds nothing.  (Separate code for the odd step, or for a
+        // steady state without load masking, makes the compiler copy the 256 accumulators between paths.)
+        constexpr int NM = M16 * N16, NF = M16 + N16;
+        static_assert(KSTEPS == 4 && STAGES == 2 && T::NLA <= NM - NF && T::NLB <= NM - NF, "burst schedule assumptions");
+        static_assert(T::B_BYTES + 7 * 16 * BK * 2 < 65536 && T::B_BYTES + 32 * BN * 2 + 4 * BN * 2 < 65536, "immediate offsets");
+        // Per-lane LDS read addresses of the fragments.  K-contiguous operand: one per k-step of 32; its 16-row
+        // blocks follow 16 rows apart, which the swizzle does not see (immediate offset).  K-strided: one per
+        // 16-row block; the k-steps follow 32 k-rows apart (immediate offset).  The N-side ones include the
+        // start of the N-side ring; the M-side ones are relative to the slot (three slots: run-time rotation).
+        constexpr int NRA = A_KC ? 2 : M16, NRB = B_KC ? 2 : N16;
+        uint32_t ra16[NRA], rb16[NRB];
+#pragma unroll
+        for (int q = 0; q < NRA; ++q)
+            ra16[q] = A_KC ? frag16_off<BM, BK, true>(wm0, q, lane) : frag16_off<BM, BK, false>(wm0 + q * 16, 0, lane);
+#pragma unroll
+        for (int q = 0; q < NRB; ++q)
+            rb16[q] = smem_lds + T::b_slot_off(0) +
+                      (B_KC ? frag16_off<BN, BK, true>(wn0, q, lane) : frag16_off<BN, BK, false>(wn0 + q * 16, 0, lane));
+        // fragment f (M side first) of k-step KK2 (0 or 1): M side from the tile at LDS address sa, N side from
+        // N-side slot SLOT
+        auto read_frag16 = [&](auto kk_tag, auto slot_tag, auto f_tag, bf16x8_t (&af)[M16], bf16x8_t (&bfr)[N16], uint32_t sa) {
+            constexpr int KK2 = decltype(kk_tag)::value, SLOT = decltype(slot_tag)::value, f = decltype(f_tag)::value;
+            static_assert(KK2 < 2 && SLOT < 2 && f < NF, "fragment index");
+            if constexpr (f < M16) {
+                if constexpr (A_KC) af[f] = lds_read_b128<f * 16 * BK * 2>(sa + ra16[KK2]);
+                else af[f] = lds_read_tr<KK2 * 32 * BM * 2, 4 * BM * 2>(sa + ra16[f]);
+            } else {
+                constexpr int j = f - M16;
+                if constexpr (B_KC) bfr[j] = lds_read_b128<SLOT * T::B_BYTES + j * 16 * BK * 2>(rb16[KK2]);
+                else bfr[j] = lds_read_tr<SLOT * T::B_BYTES + KK2 * 32 * BN * 2, 4 * BN * 2>(rb16[j]);
+            }
+        };
+        // MFMAs of the k-step held in (xa, xb); fragments of k-step KK2 of (sa, N-side slot SLOT) -> (na, nb),
+        // first the ones the next burst starts with (M block 0, then every N block, then the other M blocks);
+        // the loads of one K step of the M side (SIDE 0) or N side (SIDE 1) into `tile`
+        auto burst16 = [&](auto kk_tag, auto slot_tag, auto side_tag, const bf16x8_t (&xa)[M16],
+                           const bf16x8_t (&xb)[N16], bf16x8_t (&na)[M16], bf16x8_t (&nb)[N16], uint32_t sa, char* tile) {
+            constexpr int SIDE = decltype(side_tag)::value;
+            constexpr int NL = SIDE == 0 ? T::NLA : T::NLB;
+            constexpr int LS = (NM - NF) / NL;
             static_for<NM>([&](auto nt) {
                 constexpr int n = decltype(nt)::value;
-                constexpr int i = n / NT, j = n % NT;
-                acc[i][j] = E::mfma(xb[j], xa[i], acc[i][j]);
+                constexpr int i = n / N16, j = n % N16;
+                acc16[i][j] = E::mfma16(xb[j], xa[i], acc16[i][j]);
                 if constexpr (n < NF) {
-                    read_frag(kk_tag, nt, na, nb, sa, sb);
-                } else {
-                    // the DN loads spread evenly over the MFMAs that have no fragment read behind them
-                    constexpr int lo = ((n - NF) * DN + (NM - NF) - 1) / (NM - NF);
-                    constexpr int hi = ((n + 1 - NF) * DN + (NM - NF) - 1) / (NM - NF);
-                    static_for<hi - lo>([&](auto dt) {
-                        constexpr int t = D0 + lo + decltype(dt)::value;
-                        if constexpr (SIDE == 0) {
-                            ca.template issue_one<t>(tile, wave);
-                            if constexpr (t == T::NLA - 1) advance_a();
-                        } else {
-                            cb.template issue_one<t>(tile, wave);
-                            if constexpr (t == T::NLB - 1) advance_b();
-                        }
-                    });
+                    constexpr int f = (n == 0) ? 0 : (n <= N16 ? M16 + n - 1 : n - N16);
+                    read_frag16(kk_tag, slot_tag, std::integral_constant<int, f>{}, na, nb, sa);
+                } else if constexpr ((n - NF) % LS == 0 && (n - NF) / LS < NL) {
+                    constexpr int t = (n - NF) / LS;
+                    if constexpr (SIDE == 0) {
+                        ca.template issue_one<t>(tile, wave);
+                        if constexpr (t == T::NLA - 1) advance_a();
+                    } else {
+                        cb.template issue_one<t>(tile, wave);
+                        if constexpr (t == T::NLB - 1) advance_b();
+                    }
                 }
                 __builtin_amdgcn_sched_barrier(0);
             });
         };
         typedef std::integral_constant<int, 0> SideA;
         typedef std::integral_constant<int, 1> SideB;
-        typedef std::integral_constant<int, 0> I0;
-        typedef std::integral_constant<int, HA> IHA;
-        typedef std::integral_constant<int, T::NLA - HA> IRA;
-        typedef std::integral_constant<int, HB> IHB;
-        typedef std::integral_constant<int, T::NLB - HB> IRB;
-        // before the loop: M side steps 0 and 1, N side step 0 and the first half of step 1
-        ca.issue_all(smem + T::a_slot_off(0), wave);
-        advance_a();
-        cb.issue_all(smem + T::b_slot_off(0), wave);
-        advance_b();
-        ca.issue_all(smem + T::a_slot_off(1), wave);
-        advance_a();
-        static_for<HB>([&](auto t) { cb.template issue_one<decltype(t)::value>(smem + T::b_slot_off(1), wave); });
-        wait_vmcnt<T::NLA + HB>();                     // own share of step 0 landed
-        __builtin_amdgcn_s_barrier();                  // all of step 0 landed
-        frags(K0{}, a0, b0, 0);
+        bf16x8_t fa0[M16], fb0[N16], fa1[M16], fb1[N16];
         int sa_cur = 0, sa_nxt = 1, sa_fill = 2;       // M-side slots of steps u, u+1, u+2 (mod 3)
-        for (int u = 0; u < nsteps; ++u) {
-            const uint32_t sa = smem_lds + T::a_slot_off(sa_cur), sb = smem_lds + T::b_slot_off(u & 1);
-            const uint32_t sa1 = smem_lds + T::a_slot_off(sa_nxt), sb1 = smem_lds + T::b_slot_off((u + 1) & 1);
+        // K step u, u mod 2 == PAR
+        auto kstep = [&](auto par_tag) {
+            constexpr int PAR = decltype(par_tag)::value;
+            typedef std::integral_constant<int, PAR> Cur;
+            typedef std::integral_constant<int, PAR ^ 1> Nxt;
+            const uint32_t sa = smem_lds + T::a_slot_off(sa_cur), sa1 = smem_lds + T::a_slot_off(sa_nxt);
             wait_lgkmcnt<0>();
             __builtin_amdgcn_sched_barrier(0);
-            // step u, k-step 0; rest of the N side of step u+1
-            burst(K1{}, SideB{}, IHB{}, IRB{}, a0, b0, a1, b1, sa, sb, smem + T::b_slot_off((u + 1) & 1));
-            wait_lgkmcnt<0>();
-            __builtin_amdgcn_sched_barrier(0);
-            // k-step 1; M side of step u+2, first half
-            burst(K2{}, SideA{}, I0{}, IHA{}, a1, b1, a0, b0, sa, sb, smem + T::a_slot_off(sa_fill));
-            wait_lgkmcnt<0>();
-            __builtin_amdgcn_sched_barrier(0);
-            // k-step 2; M side of step u+2, second half
-            burst(K3{}, SideA{}, IHA{}, IRA{}, a0, b0, a1, b1, sa, sb, smem + T::a_slot_off(sa_fill));
+            // k-step 0; fragments of k-step 1; M side of step u+2
+            burst16(K1{}, Cur{}, SideA{}, fa0, fb0, fa1, fb1, sa, smem + T::a_slot_off(sa_fill));
             // Everything but the M side of step u+2 has landed, i.e. all of step u+1 (own share); own
             // reads of step u are done.  After the barrier step u+1 is visible to all and the slots of
             // step u may be refilled.
@@ -527,10 +575,26 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
             wait_lgkmcnt<0>();
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);          // no MFMA may move above the waits
-            // k-step 3 and the first fragments of step u+1; N side of step u+2, first half
-            burst(K0{}, SideB{}, I0{}, IHB{}, a1, b1, a0, b0, sa1, sb1, smem + T::b_slot_off(u & 1));
+            // k-step 1; first fragments of step u+1; N side of step u+2
+            burst16(K0{}, Nxt{}, SideB{}, fa1, fb1, fa0, fb0, sa1, smem + T::b_slot_off(PAR));
             const int t = sa_cur;
             sa_cur = sa_nxt; sa_nxt = sa_fill; sa_fill = t;
+        };
+        // before the loop: both sides of steps 0 and 1
+        ca.issue_all(smem + T::a_slot_off(0), wave);
+        advance_a();
+        cb.issue_all(smem + T::b_slot_off(0), wave);
+        advance_b();
+        ca.issue_all(smem + T::a_slot_off(1), wave);
+        advance_a();
+        cb.issue_all(smem + T::b_slot_off(1), wave);
+        advance_b();
+        wait_vmcnt<T::NLA + T::NLB>();                 // own share of step 0 landed
+        __builtin_amdgcn_s_barrier();                  // all of step 0 landed
+        static_for<NF>([&](auto ft) { read_frag16(K0{}, K0{}, ft, fa0, fb0, smem_lds + T::a_slot_off(0)); });
+        for (int u = 0; u < nsteps; u += 2) {
+            kstep(K0{});
+            kstep(K1{});
         }
         wait_vmcnt<0>();
         wait_lgkmcnt<0>();
@@ -652,6 +716,65 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
     __syncthreads();
 
     // ------------------------------------------------------------------------------ epilogues
+    if constexpr (MI16) {
+        // 16x16 accumulator tiles: the lane holds n = 4*(lane >> 4) .. +3 of row m = lane & 15 of tile
+        // (i, j).  Two tile rows (32 rows of C) are staged through LDS at a time, then written as whole
+        // 16-byte vectors along N.  16-bit outputs only (the launcher sends nothing else here).
+        static_assert(EPI == EPI_STORE_BF16 || EPI == EPI_COMPOSE, "the 16x16x32 path stores 16-bit tiles");
+        constexpr int ROW_BYTES = T::WN * 2 + 16;
+        constexpr int CHUNKS_PER_ROW = T::WN * 2 / 16;
+        constexpr int ROWS_PER_PASS = 64 / CHUNKS_PER_ROW;
+        char* stg = smem + wave * T::EPI_BYTES_PER_WAVE;
+        const int l16 = lane & 15, lq = lane >> 4;
+        // EPI_COMPOSE: pass 0 writes colscale[n] * acc (+ bias) to C (y = g (.) inner), pass 1 writes acc to C2
+        // EPI_STORE_BF16 with a second output: pass 1 writes alpha2 * acc to C2
+        const int npass = (p.c2 != nullptr) ? 2 : 1;
+        for (int pass = 0; pass < npass; ++pass) {
+            char* cbase = reinterpret_cast<char*>(pass == 0 ? p.c : p.c2);
+#pragma unroll
+            for (int ib = 0; ib < M16 / 2; ++ib) {
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int half = 0; half < 2; ++half)
+#pragma unroll
+                    for (int j = 0; j < N16; ++j) {
+                        const int col = j * 16 + lq * 4;
+                        const f32x4_t a = acc16[ib * 2 + half][j];
+                        float v0, v1, v2, v3;
+                        if (EPI == EPI_COMPOSE) {
+                            float4 g4 = make_float4(1.f, 1.f, 1.f, 1.f);
+                            uint2 b4 = make_uint2(0u, 0u);
+                            if (pass == 0) {
+                                const int ng = n0 + wn0 + col;
+                                g4 = (ng < p.N) ? *reinterpret_cast<const float4*>(p.colscale + ng) : make_float4(0.f, 0.f, 0.f, 0.f);
+                                if (p.colbias && ng < p.N) b4 = *reinterpret_cast<const uint2*>(p.colbias + ng);
+                            }
+                            v0 = fmaf(g4.x, a[0], E::lo(b4.x)); v1 = fmaf(g4.y, a[1], E::hi(b4.x));
+                            v2 = fmaf(g4.z, a[2], E::lo(b4.y)); v3 = fmaf(g4.w, a[3], E::hi(b4.y));
+                        } else {
+                            const float al = (pass == 0) ? p.alpha : p.alpha2;
+                            v0 = al * a[0]; v1 = al * a[1]; v2 = al * a[2]; v3 = al * a[3];
+                        }
+                        uint2 o;
+                        o.x = E::pack2(v0, v1);
+                        o.y = E::pack2(v2, v3);
+                        *reinterpret_cast<uint2*>(stg + (half * 16 + l16) * ROW_BYTES + col * 2) = o;
+                    }
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int ps = 0; ps < 32 / ROWS_PER_PASS; ++ps) {
+                    const int row = ps * ROWS_PER_PASS + lane / CHUNKS_PER_ROW;
+                    const int ch = lane % CHUNKS_PER_ROW;
+                    uint4 v = *reinterpret_cast<const uint4*>(stg + row * ROW_BYTES + ch * 16);
+                    const int mg = m0 + wm0 + ib * 32 + row;
+                    const int ng = n0 + wn0 + ch * 8;
+                    if (mg < p.M && ng < p.N)
+                        *reinterpret_cast<uint4*>(cbase + ((int64_t)mg * p.ldc + ng) * 2) = v;
+                }
+            }
+        }
+        return;
+    } else {
     // (a row-dot instance may carry a second problem that stores its fp32 tile instead: the Gram matrix riding
     // along with the cross term; it falls through to the store epilogue below)
     if (EPI == EPI_ROWDOT && p.epilogue == EPI_ROWDOT) {
@@ -755,6 +878,7 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
         }
     }
     }
+    }  // !MI16
 }
 
 template <class T>
