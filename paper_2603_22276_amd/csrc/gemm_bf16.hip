@@ -171,6 +171,11 @@ __device__ __forceinline__ uint32_t frag16_off(int row0, int k32, int lane)
 // Loads go through a buffer descriptor: an offset at or beyond num_records yields zeros, which
 // covers rows past the end of the operand; rows or k out of range for other reasons get the offset
 // 0xFFFFFFFF.  The K advance travels in the scalar offset.  The LW waves of the workgroup share the tile.
+// The issue path itself has no vector arithmetic: a select feeding a load's address, with other vector
+// instructions around it, stalls a wave that is otherwise issuing back-to-back 16-cycle MFMAs for several
+// MFMAs' time (register-resident probe: 64 MFMAs + 8 such loads + 16 additions 1670 cycles against 1060
+// with the loads taking their offsets as they are).  The k mask of a ragged last K step is therefore
+// folded into the offsets once, before that step, and an exhausted cursor gets an empty descriptor.
 template <int ROWS, int BK, int NL, int LW, bool KCONTIG>
 struct OperandLoader {
     static constexpr int CPR = BK / 8;
@@ -213,21 +218,26 @@ struct OperandLoader {
             if (i == 0) kl0 = k;
         }
     }
-    // Branch-free issue of one K step: chunks whose k index is at or beyond `krem` (the k left in the
-    // segment; <= 0 once the schedule is exhausted) are pushed out of range and load zeros.
+    // Before a ragged last K step with `krem` k left: chunks whose k index is at or beyond it are pushed
+    // out of range and load zeros.
+    static __device__ __forceinline__ void mask_tail(uint32_t (&vo)[NL], int kl0, int krem)
+    {
+#pragma unroll
+        for (int i = 0; i < NL; ++i)
+            if (kl0 + i * K_INC >= krem) vo[i] = 0xFFFFFFFFu;
+    }
+    // load I of a K step; `off` is its entry of the offset table
     template <int I>
-    static __device__ __forceinline__ void issue_one(char* tile, __amdgpu_buffer_rsrc_t rs, const uint32_t (&vo)[NL],
-                                                     int kl0, uint32_t soffset, int krem, int lw)
+    static __device__ __forceinline__ void issue_one(char* tile, __amdgpu_buffer_rsrc_t rs, uint32_t off, uint32_t soffset,
+                                                     int lw)
     {
         static_assert(I >= 0 && I < NL, "load index");
-        const uint32_t off = (kl0 < krem - I * K_INC) ? vo[I] : 0xFFFFFFFFu;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_ptr_t)(tile + (I * LW + lw) * 1024), 16, off, soffset, 0,
-                                                 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_ptr_t)(tile + (I * LW + lw) * 1024), 16, off, soffset, 0, 0);
     }
     static __device__ __forceinline__ void issue(char* tile, __amdgpu_buffer_rsrc_t rs, const uint32_t (&vo)[NL],
-                                                 int kl0, uint32_t soffset, int krem, int lw)
+                                                 uint32_t soffset, int lw)
     {
-        static_for<NL>([&](auto it) { issue_one<decltype(it)::value>(tile, rs, vo, kl0, soffset, krem, lw); });
+        static_for<NL>([&](auto it) { issue_one<decltype(it)::value>(tile, rs, vo[decltype(it)::value], soffset, lw); });
     }
 };
 
@@ -239,23 +249,25 @@ struct Cursor {
     int kl0;
     __amdgpu_buffer_rsrc_t rs;
     uint32_t so, so_step;   // scalar byte offset of the next K step and its increment
-    int krem;               // k still to load in the segment (<= 0: exhausted, every further load brings zeros)
-    __device__ __forceinline__ void open(const bf16_t* base, int64_t ld, int K, int row0, int rows, int k_first,
-                                         int k_last, int wave, int lane)
+    __device__ __forceinline__ void open(const bf16_t* base, int64_t ld, int K, int row0, int rows, int k_first, int wave,
+                                         int lane)
     {
         rs = L::make_rsrc(base, ld, rows, K);
         L::offsets(vo, kl0, ld, row0, rows, wave, lane);
         so_step = KCONTIG ? (uint32_t)(BK * 2) : (uint32_t)(BK * ld * 2);
         so = KCONTIG ? (uint32_t)(k_first * 2) : (uint32_t)((int64_t)k_first * ld * 2);
-        krem = (k_last < K ? k_last : K) - k_first;
     }
+    // the next K step is the ragged last one of its segment, with krem k left
+    __device__ __forceinline__ void mask_tail(int krem) { L::mask_tail(vo, kl0, krem); }
+    // nothing left to load: every further load brings zeros
+    __device__ __forceinline__ void exhaust(const bf16_t* base) { rs = L::make_rsrc(base, 0, 0, 0); }
     template <int I>
     __device__ __forceinline__ void issue_one(char* tile, int wave) const
     {
-        L::template issue_one<I>(tile, rs, vo, kl0, so, krem, wave);
+        L::template issue_one<I>(tile, rs, vo[I], so, wave);
     }
-    __device__ __forceinline__ void issue_all(char* tile, int wave) const { L::issue(tile, rs, vo, kl0, so, krem, wave); }
-    __device__ __forceinline__ void step() { so += so_step; krem -= BK; }
+    __device__ __forceinline__ void issue_all(char* tile, int wave) const { L::issue(tile, rs, vo, so, wave); }
+    __device__ __forceinline__ void step() { so += so_step; }
 };
 
 struct TileCoord { int tm, tn, z; };
@@ -365,34 +377,54 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
     const bool want_bsq = (EPI == EPI_ROWDOT) && (p.base_sq_partial != nullptr) && (tc.tn == 0);
     typedef OperandLoader<BM, BK, T::NLA, T::WAVES, A_KC> LA;
     typedef OperandLoader<BN, BK, T::NLB, T::WAVES, B_KC> LB;
-    // One cursor per operand; each moves to the next segment (or to "exhausted") on its own.
-    // Segment 0 covers K steps [t_begin, min(t_end, kt0_total)); segment 1 (never split) the rest.
+    // One cursor per operand; each walks its own schedule.  Segment 0 covers K steps
+    // [t_begin, min(t_end, kt0_total)); segment 1 (never split) the rest.  Phases of a schedule: 0 = the
+    // whole K steps of segment 0, 1 = its ragged last step, 2 and 3 = the same for segment 1, 4 = exhausted.
+    // A counter per cursor runs down to the end of the phase; only then is anything but the scalar offset
+    // touched (offsets masked for a ragged step, the next segment opened, the descriptor emptied).
     Cursor<LA, T::NLA, BK, A_KC> ca;
     Cursor<LB, T::NLB, BK, B_KC> cb;
     const bool has_seg1 = (p.nseg > 1) && (t_end > kt0_total);
-    const int seg0_k0 = t_begin * BK, seg0_k1 = (t_end < kt0_total ? t_end : kt0_total) * BK;
+    const int seg0_k0 = t_begin * BK;
+    const int seg0_k1 = (t_end < kt0_total ? t_end : kt0_total) * BK;
+    int len0 = (seg0_k1 < p.seg[0].K ? seg0_k1 : p.seg[0].K) - seg0_k0;   // k of segment 0 in this K slice
+    if (len0 < 0) len0 = 0;
+    const int len1 = has_seg1 ? p.seg[1].K : 0;
+    const int whole0 = len0 / BK, rag0 = len0 % BK, whole1 = len1 / BK, rag1 = len1 % BK;
     auto open_a = [&](int sidx) {
         const GemmSeg& sg = p.seg[sidx];
-        ca.open(sg.a, sg.lda, sg.K, m0, p.M, sidx ? 0 : seg0_k0, sidx ? sg.K : seg0_k1, wave, lane);
+        ca.open(sg.a, sg.lda, sg.K, m0, p.M, sidx ? 0 : seg0_k0, wave, lane);
     };
     auto open_b = [&](int sidx) {
         const GemmSeg& sg = p.seg[sidx];
-        cb.open(sg.b, sg.ldb, sg.K, n0, p.N, sidx ? 0 : seg0_k0, sidx ? sg.K : seg0_k1, wave, lane);
+        cb.open(sg.b, sg.ldb, sg.K, n0, p.N, sidx ? 0 : seg0_k0, wave, lane);
     };
+    int a_ph = -1, b_ph = -1, a_left = 0, b_left = 0;   // phase and K steps left in it (negative: never ends)
+    // move a cursor to its next non-empty phase
+    auto next_phase = [&](auto& cur, int& ph, int& left, auto&& open1, const bf16_t* base0) {
+        const int from = ph;
+        if (from < 0 && whole0 > 0) { ph = 0; left = whole0; return; }
+        if (from < 1 && rag0 > 0) { cur.mask_tail(rag0); ph = 1; left = 1; return; }
+        if (from < 2 && (whole1 | rag1) != 0) open1();
+        if (from < 2 && whole1 > 0) { ph = 2; left = whole1; return; }
+        if (from < 3 && rag1 > 0) { cur.mask_tail(rag1); ph = 3; left = 1; return; }
+        cur.exhaust(base0);
+        ph = 4;
+        left = -1;
+    };
+    auto next_phase_a = [&]() { next_phase(ca, a_ph, a_left, [&]() { open_a(1); }, p.seg[0].a); };
+    auto next_phase_b = [&]() { next_phase(cb, b_ph, b_left, [&]() { open_b(1); }, p.seg[0].b); };
     open_a(0);
     open_b(0);
-    // K steps each cursor still has to issue before it moves on to segment 1 (counts down; never reaches
-    // zero again once it is negative)
-    const int seg0_steps = (t_end < kt0_total ? t_end : kt0_total) - t_begin;
-    int a_left = (has_seg1 && seg0_steps > 0) ? seg0_steps : -1, b_left = a_left;
-    if (has_seg1 && seg0_steps <= 0) { open_a(1); open_b(1); }
+    next_phase_a();
+    next_phase_b();
     auto advance_a = [&]() {
         ca.step();
-        if (--a_left == 0) open_a(1);
+        if (--a_left == 0) next_phase_a();
     };
     auto advance_b = [&]() {
         cb.step();
-        if (--b_left == 0) open_b(1);
+        if (--b_left == 0) next_phase_b();
     };
     auto issue = [&](int slot) {   // every load of the next K step of both operands
         ca.issue_all(smem + T::a_slot_off(slot), wave);
