@@ -26,9 +26,6 @@
 #include <type_traits>
 #include <utility>
 
-#ifndef DORA_RS
-#define DORA_RS 2
-#endif
 namespace dora {
 namespace {
 
@@ -549,7 +546,9 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
             constexpr int KK2 = decltype(kk_tag)::value, SLOT = decltype(slot_tag)::value, f = decltype(f_tag)::value;
             static_assert(KK2 < 2 && SLOT < 2 && f < NF, "fragment index");
             if constexpr (f < M16) {
-                if constexpr (A_KC) af[f] = lds_read_b128<f * 16 * BK * 2>(sa + ra16[KK2]);
+                // (K-contiguous: the caller passes the address of the k-step, slot and per-lane part added up
+                // ahead of the burst; an addition right in front of the read it feeds holds the wave up)
+                if constexpr (A_KC) af[f] = lds_read_b128<f * 16 * BK * 2>(sa);
                 else af[f] = lds_read_tr<KK2 * 32 * BM * 2, 4 * BM * 2>(sa + ra16[f]);
             } else {
                 constexpr int j = f - M16;
@@ -594,7 +593,8 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
             constexpr int PAR = decltype(par_tag)::value;
             typedef std::integral_constant<int, PAR> Cur;
             typedef std::integral_constant<int, PAR ^ 1> Nxt;
-            const uint32_t sa = smem_lds + T::a_slot_off(sa_cur), sa1 = smem_lds + T::a_slot_off(sa_nxt);
+            uint32_t sa = smem_lds + T::a_slot_off(sa_cur), sa1 = smem_lds + T::a_slot_off(sa_nxt);
+            if constexpr (A_KC) { sa += ra16[1]; sa1 += ra16[0]; }
             wait_lgkmcnt<0>();
             __builtin_amdgcn_sched_barrier(0);
             // k-step 0; fragments of k-step 1; M side of step u+2
@@ -623,7 +623,7 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
         advance_b();
         wait_vmcnt<T::NLA + T::NLB>();                 // own share of step 0 landed
         __builtin_amdgcn_s_barrier();                  // all of step 0 landed
-        static_for<NF>([&](auto ft) { read_frag16(K0{}, K0{}, ft, fa0, fb0, smem_lds + T::a_slot_off(0)); });
+        static_for<NF>([&](auto ft) { read_frag16(K0{}, K0{}, ft, fa0, fb0, smem_lds + T::a_slot_off(0) + (A_KC ? ra16[0] : 0u)); });
         for (int u = 0; u < nsteps; u += 2) {
             kstep(K0{});
             kstep(K1{});
