@@ -758,11 +758,24 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
         constexpr int ROWS_PER_PASS = 64 / CHUNKS_PER_ROW;
         char* stg = smem + wave * T::EPI_BYTES_PER_WAVE;
         const int l16 = lane & 15, lq = lane >> 4;
+        // Everything the stores need from the argument block, read once (left in place, each store would
+        // fetch its share from memory again); per lane, one pointer that walks down the rows and the number
+        // of rows below its first one that exist (zero when its columns do not).
+        const int pM = p.M, pN = p.N;
+        const int64_t row_step = (int64_t)p.ldc * 2 * ROWS_PER_PASS;
+        const float alpha[2] = {p.alpha, p.alpha2};
+        char* const cptr[2] = {reinterpret_cast<char*>(p.c), reinterpret_cast<char*>(p.c2)};
+        const float* const colscale = p.colscale;
+        const bf16_t* const colbias = p.colbias;
+        const int ch = lane % CHUNKS_PER_ROW;
+        const int mg0 = m0 + wm0 + lane / CHUNKS_PER_ROW, ng0 = n0 + wn0 + ch * 8;
+        const int rows_left = (ng0 < pN) ? pM - mg0 : 0;
         // EPI_COMPOSE: pass 0 writes colscale[n] * acc (+ bias) to C (y = g (.) inner), pass 1 writes acc to C2
         // EPI_STORE_BF16 with a second output: pass 1 writes alpha2 * acc to C2
-        const int npass = (p.c2 != nullptr) ? 2 : 1;
+        const int npass = (cptr[1] != nullptr) ? 2 : 1;
         for (int pass = 0; pass < npass; ++pass) {
-            char* cbase = reinterpret_cast<char*>(pass == 0 ? p.c : p.c2);
+            char* ptr = cptr[pass] + ((int64_t)mg0 * p.ldc + ng0) * 2;
+            const float al = alpha[pass];
 #pragma unroll
             for (int ib = 0; ib < M16 / 2; ++ib) {
                 __builtin_amdgcn_wave_barrier();
@@ -778,13 +791,12 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
                             uint2 b4 = make_uint2(0u, 0u);
                             if (pass == 0) {
                                 const int ng = n0 + wn0 + col;
-                                g4 = (ng < p.N) ? *reinterpret_cast<const float4*>(p.colscale + ng) : make_float4(0.f, 0.f, 0.f, 0.f);
-                                if (p.colbias && ng < p.N) b4 = *reinterpret_cast<const uint2*>(p.colbias + ng);
+                                g4 = (ng < pN) ? *reinterpret_cast<const float4*>(colscale + ng) : make_float4(0.f, 0.f, 0.f, 0.f);
+                                if (colbias && ng < pN) b4 = *reinterpret_cast<const uint2*>(colbias + ng);
                             }
                             v0 = fmaf(g4.x, a[0], E::lo(b4.x)); v1 = fmaf(g4.y, a[1], E::hi(b4.x));
                             v2 = fmaf(g4.z, a[2], E::lo(b4.y)); v3 = fmaf(g4.w, a[3], E::hi(b4.y));
                         } else {
-                            const float al = (pass == 0) ? p.alpha : p.alpha2;
                             v0 = al * a[0]; v1 = al * a[1]; v2 = al * a[2]; v3 = al * a[3];
                         }
                         uint2 o;
@@ -796,12 +808,9 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
 #pragma unroll
                 for (int ps = 0; ps < 32 / ROWS_PER_PASS; ++ps) {
                     const int row = ps * ROWS_PER_PASS + lane / CHUNKS_PER_ROW;
-                    const int ch = lane % CHUNKS_PER_ROW;
                     uint4 v = *reinterpret_cast<const uint4*>(stg + row * ROW_BYTES + ch * 16);
-                    const int mg = m0 + wm0 + ib * 32 + row;
-                    const int ng = n0 + wn0 + ch * 8;
-                    if (mg < p.M && ng < p.N)
-                        *reinterpret_cast<uint4*>(cbase + ((int64_t)mg * p.ldc + ng) * 2) = v;
+                    if (ib * 32 + ps * ROWS_PER_PASS < rows_left) *reinterpret_cast<uint4*>(ptr) = v;
+                    ptr += row_step;
                 }
             }
         }
