@@ -816,23 +816,35 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
         }
         return;
     } else {
+    // Everything the epilogues need from the argument block, read once: left in place, every use would fetch
+    // its share from memory again (the block is selected at run time), each fetch a wait of its own.
+    const int pM = p.M, pN = p.N, p_ksplit = p.ksplit, p_epilogue = p.epilogue;
+    const int64_t p_ldc = p.ldc, p_ld_rowdot = p.ld_rowdot;
+    const float p_alpha = p.alpha, p_alpha2 = p.alpha2;
+    void* const p_c = p.c;
+    void* const p_c2 = p.c2;
+    const float* const p_colscale = p.colscale;
+    const bf16_t* const p_colbias = p.colbias;
+    const bf16_t* const p_rowdot = p.rowdot;
+    float* const p_rowdot_partial = p.rowdot_partial;
+    float* const p_base_sq_partial = p.base_sq_partial;
     // (a row-dot instance may carry a second problem that stores its fp32 tile instead: the Gram matrix riding
     // along with the cross term; it falls through to the store epilogue below)
-    if (EPI == EPI_ROWDOT && p.epilogue == EPI_ROWDOT) {
+    if (EPI == EPI_ROWDOT && p_epilogue == EPI_ROWDOT) {
         float* red = reinterpret_cast<float*>(smem);          // [WGN][BM] row-dot, then [WGN][BM] base_sq
         float* red2 = red + T::WGN * BM;
 #pragma unroll
         for (int i = 0; i < MT; ++i) {
             const int mg = m0 + wm0 + i * 32 + l32;
             float rs = 0.f;
-            if (mg < p.M) {
+            if (mg < pM) {
 #pragma unroll
                 for (int j = 0; j < NT; ++j)
 #pragma unroll
                     for (int b = 0; b < 4; ++b) {
                         const int ng = n0 + wn0 + j * 32 + b * 8 + lh * 4;
-                        if (ng < p.N) {
-                            uint2 rv = *reinterpret_cast<const uint2*>(p.rowdot + (int64_t)mg * p.ld_rowdot + ng);
+                        if (ng < pN) {
+                            uint2 rv = *reinterpret_cast<const uint2*>(p_rowdot + (int64_t)mg * p_ld_rowdot + ng);
                             rs = fmaf(acc[i][j][b * 4 + 0], E::lo(rv.x), rs);
                             rs = fmaf(acc[i][j][b * 4 + 1], E::hi(rv.x), rs);
                             rs = fmaf(acc[i][j][b * 4 + 2], E::lo(rv.y), rs);
@@ -848,11 +860,11 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
             }
         }
         __syncthreads();
-        if (tid < BM && m0 + tid < p.M) {
+        if (tid < BM && m0 + tid < pM) {
             float v = red[tid], q = red2[tid];
             for (int w = 1; w < T::WGN; ++w) { v += red[w * BM + tid]; q += red2[w * BM + tid]; }
-            p.rowdot_partial[(int64_t)(tc.z * tiles_n + tc.tn) * p.M + m0 + tid] = v;
-            if (want_bsq) p.base_sq_partial[(int64_t)tc.z * p.M + m0 + tid] = q;
+            p_rowdot_partial[(int64_t)(tc.z * tiles_n + tc.tn) * pM + m0 + tid] = v;
+            if (want_bsq) p_base_sq_partial[(int64_t)tc.z * pM + m0 + tid] = q;
         }
         return;
     }
@@ -869,10 +881,10 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
     // (the per-column scale and bias are re-read for every 32-row band: sixteen float4 per lane kept
     // across the whole epilogue would not fit beside 256 accumulators)
     // EPI_STORE_BF16 with a second output: pass 1 writes alpha2 * acc to C2
-    const int npass = ((EPI == EPI_COMPOSE || EPI == EPI_STORE_BF16) && p.c2 != nullptr) ? 2 : 1;
+    const int npass = ((EPI == EPI_COMPOSE || EPI == EPI_STORE_BF16) && p_c2 != nullptr) ? 2 : 1;
     for (int pass = 0; pass < npass; ++pass) {
-    char* cbase = reinterpret_cast<char*>(pass == 0 ? p.c : p.c2) +
-                  (p.ksplit > 1 ? (int64_t)tc.z * p.M * p.ldc * ESZ : 0);
+    char* cbase = reinterpret_cast<char*>(pass == 0 ? p_c : p_c2) +
+                  (p_ksplit > 1 ? (int64_t)tc.z * pM * p_ldc * ESZ : 0);
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
         __builtin_amdgcn_wave_barrier();
@@ -887,13 +899,13 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
                     uint2 b4 = make_uint2(0u, 0u);
                     if (pass == 0) {
                         const int ng = n0 + wn0 + col;
-                        g4 = (ng < p.N) ? *reinterpret_cast<const float4*>(p.colscale + ng) : make_float4(0.f, 0.f, 0.f, 0.f);
-                        if (p.colbias && ng < p.N) b4 = *reinterpret_cast<const uint2*>(p.colbias + ng);
+                        g4 = (ng < pN) ? *reinterpret_cast<const float4*>(p_colscale + ng) : make_float4(0.f, 0.f, 0.f, 0.f);
+                        if (p_colbias && ng < pN) b4 = *reinterpret_cast<const uint2*>(p_colbias + ng);
                     }
                     v0 = fmaf(g4.x, acc[i][j][b * 4 + 0], E::lo(b4.x)); v1 = fmaf(g4.y, acc[i][j][b * 4 + 1], E::hi(b4.x));
                     v2 = fmaf(g4.z, acc[i][j][b * 4 + 2], E::lo(b4.y)); v3 = fmaf(g4.w, acc[i][j][b * 4 + 3], E::hi(b4.y));
                 } else {
-                    const float al = (pass == 0) ? p.alpha : p.alpha2;
+                    const float al = (pass == 0) ? p_alpha : p_alpha2;
                     v0 = al * acc[i][j][b * 4 + 0]; v1 = al * acc[i][j][b * 4 + 1];
                     v2 = al * acc[i][j][b * 4 + 2]; v3 = al * acc[i][j][b * 4 + 3];
                 }
@@ -914,8 +926,8 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
             uint4 v = *reinterpret_cast<const uint4*>(stg + row * ROW_BYTES + ch * 16);
             const int mg = m0 + wm0 + i * 32 + row;
             const int ng = n0 + wn0 + ch * (16 / ESZ);
-            if (mg < p.M && ng < p.N)
-                *reinterpret_cast<uint4*>(cbase + ((int64_t)mg * p.ldc + ng) * ESZ) = v;
+            if (mg < pM && ng < pN)
+                *reinterpret_cast<uint4*>(cbase + ((int64_t)mg * p_ldc + ng) * ESZ) = v;
         }
     }
     }
