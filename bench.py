@@ -527,31 +527,61 @@ def c3_extras(args, torch, D, G):
         out["other_forward_path"] = {
             "forward_path": "base, lora, compose pass" if args.fused_forward else "fused epilogue",
             "ms_per_step_without_event_pairs": ms_other, "tokens_per_s": wl.tokens / (ms_other * 1e-3)}
+        library = {}
+        cfg = mod.cfg
+        if cfg.dtype == "bf16":
+            # the vendor library's GEMM on this module's own x and W, for context (HIP events on torch's stream)
+            yy = torch.empty((cfg.tokens, cfg.d_out), dtype=torch.bfloat16, device=G.DEV)
+            for _ in range(3):
+                torch.matmul(mod.x, mod.W.t(), out=yy)
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(7)]
+            for e0, e1 in evs:
+                e0.record()
+                torch.matmul(mod.x, mod.W.t(), out=yy)
+                e1.record()
+            torch.cuda.synchronize()
+            lib_us = sorted(e0.elapsed_time(e1) * 1e3 for e0, e1 in evs)[len(evs) // 2]
+            library["library_matmul_x_Wt_us"] = lib_us
+            library["library_matmul_x_Wt_TFLOPs"] = 2.0 * cfg.tokens * cfg.d_out * cfg.d_in / lib_us / 1e6
+            del yy
         probe_bytes = 512 * 2 ** 20
         src = torch.empty(probe_bytes, dtype=torch.uint8, device=G.DEV).fill_(1)
         dst = torch.empty_like(src)
         sink = torch.zeros(512, dtype=torch.float32, device=G.DEV)
-        probe_iters, probe_wgs = 512, 1024
-        for _ in range(2):
-            D.dora_probe_copy(src, dst, probe_bytes)
-            D.dora_probe_mfma(sink, probe_iters, probe_wgs)
-        torch.cuda.synchronize()
-        D.dora_trace_reset()
-        D.dora_trace_select(~0)
-        D.dora_trace_enable(True)
-        for _ in range(5):
-            D.dora_probe_copy(src, dst, probe_bytes)
-            D.dora_probe_mfma(sink, probe_iters, probe_wgs)
-        torch.cuda.synchronize()
-        D.dora_trace_enable(False)
-        D.dora_trace_collect()
-        copy_ms, copy_n = D.dora_trace_get(16)
-        mfma_ms, mfma_n = D.dora_trace_get(17)
-        out["sustained_on_this_card"] = {
-            "copy_GBps": 2.0 * probe_bytes / (copy_ms * 1e-3 / copy_n) / 1e9,
-            "mfma_bf16_TFLOPs": probe_wgs * 8 * probe_iters * 8 * 32768.0 / (mfma_ms * 1e-3 / mfma_n) / 1e12,
-            "note": "plain 16-byte-per-lane copy of 512 MiB (read + write counted) and a register-resident "
-                    "v_mfma_f32_32x32x16_bf16 loop, measured in this run"}
+        gen = torch.Generator(device=G.DEV)
+        gen.manual_seed(1234)
+        operands = {"normal": torch.randn(65536 // 2, device=G.DEV, generator=gen).to(torch.bfloat16),
+                    "zeros": torch.zeros(65536 // 2, dtype=torch.bfloat16, device=G.DEV)}
+        probe_iters, probe_wgs = 1024, 1024
+        probe_flop = probe_wgs * 4 * probe_iters * 64 * 16384.0
+
+        def traced(fn, kernel_id, reps=5):
+            for _ in range(2):
+                fn()
+            torch.cuda.synchronize()
+            D.dora_trace_reset()
+            D.dora_trace_select(~0)
+            D.dora_trace_enable(True)
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            D.dora_trace_enable(False)
+            D.dora_trace_collect()
+            ms, n = D.dora_trace_get(kernel_id)
+            return ms * 1e-3 / n
+        copy_s = traced(lambda: D.dora_probe_copy(src, dst, probe_bytes), 16)
+        mfma_s = {k: traced(lambda v=v: D.dora_probe_mfma(v, sink, probe_iters, probe_wgs), 17) for k, v in operands.items()}
+        sustained = {
+            "copy_GBps": 2.0 * probe_bytes / copy_s / 1e9,
+            "mfma_bf16_TFLOPs_normal_operands": probe_flop / mfma_s["normal"] / 1e12,
+            "mfma_bf16_TFLOPs_zero_operands": probe_flop / mfma_s["zeros"] / 1e12,
+            "note": "plain 16-byte-per-lane copy of 512 MiB (read + write counted); register-resident "
+                    "v_mfma_f32_16x16x32_bf16 loop, one wave per SIMD, on N(0,1) and on all-zero operands (the card "
+                    "is power limited: the rate depends on the operand values); library_matmul: torch.matmul (the vendor "
+                    "library) on this module's own x and W, median of 7 back-to-back launches, for context; all "
+                    "measured in this run"}
+        sustained.update(library)
+        out["sustained_on_this_card"] = sustained
         out["workspace_bytes"] = {"norm": D.dora_workspace_bytes(desc, D.PHASE_NORM),
                                   "forward": D.dora_workspace_bytes(desc, D.PHASE_FORWARD),
                                   "backward": D.dora_workspace_bytes(desc, D.PHASE_BACKWARD),

@@ -59,13 +59,17 @@ const char* dora_trace_name(int kernel_id);
  *                     multiple of 16): a plain streaming kernel that reads and writes exactly `bytes`
  *                     each - the reference against which HBM byte counters and the achieved
  *                     bandwidth of the compose passes can be scaled.
- *   dora_probe_mfma : `workgroups` workgroups of 8 wavefronts each issue iters * 8
- *                     v_mfma_f32_32x32x16_bf16 from registers (32768 flop per instruction per
- *                     wavefront): the matrix-core rate the card sustains with no memory traffic.
- *                     sink : device, fp32 [512], never written in practice.
+ *   dora_probe_mfma : `workgroups` workgroups of 4 wavefronts (one per SIMD, as in the large GEMM
+ *                     tiles) each issue iters * 64 v_mfma_f32_16x16x32_bf16 (16384 flop per
+ *                     instruction per wavefront) on 8 x 8 accumulator tiles from registers: the
+ *                     matrix-core rate the card sustains with no memory traffic.  The rate depends
+ *                     on the operand values (the card is power limited), so the caller supplies them:
+ *                     operands : device, 65536 bytes (16 fragments of 16 bytes per lane for 256
+ *                                lanes), any bf16 bit patterns; read once per wavefront.
+ *                     sink     : device, fp32 [256], never written in practice.
  */
 dora_status dora_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
-dora_status dora_probe_mfma(float* sink, int iters, int workgroups, void* stream);
+dora_status dora_probe_mfma(const void* operands, float* sink, int iters, int workgroups, void* stream);
 
 #ifdef __cplusplus
 }

@@ -71,7 +71,7 @@ def lib() -> ctypes.CDLL:
         L.dora_forward_dropout.argtypes = [dp, vp, vp, vp, vp, vp, fp, fp, vp, vp, vp, vp, fp, vp, sz, vp]
         L.dora_backward_dropout.argtypes = [dp, vp, vp, vp, vp, vp, fp, fp, vp, vp, vp, vp, fp, fp, fp, vp, sz, vp]
         L.dora_probe_copy.argtypes = [vp, vp, sz, vp]
-        L.dora_probe_mfma.argtypes = [fp, ctypes.c_int, ctypes.c_int, vp]
+        L.dora_probe_mfma.argtypes = [vp, fp, ctypes.c_int, ctypes.c_int, vp]
         for f in (L.dora_probe_copy, L.dora_probe_mfma, L.dora_norm, L.dora_norm_static, L.dora_base_sq, L.dora_norm_cached, L.dora_norm_terms, L.dora_norm_assemble, L.dora_mag_scale, L.dora_compose, L.dora_compose_backward, L.dora_project, L.dora_forward, L.dora_forward_fused,
                   L.dora_backward, L.dora_forward_dropout, L.dora_backward_dropout, L.dora_trace_collect, L.dora_trace_get):
             f.restype = ctypes.c_int
@@ -218,8 +218,8 @@ def dora_probe_copy(src, dst, nbytes: int, stream=None) -> None:
     _check(lib().dora_probe_copy(_p(src), _p(dst), int(nbytes), _stream(stream)), "dora_probe_copy")
 
 
-def dora_probe_mfma(sink, iters: int, workgroups: int, stream=None) -> None:
-    _check(lib().dora_probe_mfma(_p(sink), int(iters), int(workgroups), _stream(stream)), "dora_probe_mfma")
+def dora_probe_mfma(operands, sink, iters: int, workgroups: int, stream=None) -> None:
+    _check(lib().dora_probe_mfma(_p(operands), _p(sink), int(iters), int(workgroups), _stream(stream)), "dora_probe_mfma")
 
 
 def dora_trace_enable(on: bool) -> None:

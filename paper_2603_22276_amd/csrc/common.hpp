@@ -197,6 +197,6 @@ hipError_t launch_splitk_reduce(const float* partials, int ksplit, int64_t n, in
                                 hipStream_t st);
 
 hipError_t launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t st);
-hipError_t launch_mfma_probe(float* sink, int iters, int workgroups, hipStream_t st);
+hipError_t launch_mfma_probe(const void* operands, float* sink, int iters, int workgroups, hipStream_t st);
 
 }  // namespace dora

@@ -835,11 +835,11 @@ dora_status dora_probe_copy(const void* src, void* dst, size_t bytes, void* stre
     return DORA_OK;
 }
 
-dora_status dora_probe_mfma(float* sink, int iters, int workgroups, void* stream)
+dora_status dora_probe_mfma(const void* operands, float* sink, int iters, int workgroups, void* stream)
 {
-    DORA_REQ_PTR(sink);
+    DORA_REQ_PTR(operands); DORA_REQ_PTR(sink);
     if (iters < 0 || workgroups < 0 || workgroups > 65536) return DORA_ERR_SHAPE;
-    DORA_HIP(launch_mfma_probe(sink, iters, workgroups, (hipStream_t)stream));
+    DORA_HIP(launch_mfma_probe(operands, sink, iters, workgroups, (hipStream_t)stream));
     return DORA_OK;
 }
 

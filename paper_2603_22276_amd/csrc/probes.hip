@@ -24,24 +24,35 @@ __global__ __launch_bounds__(256) void copy_probe_kernel(const uint4* __restrict
     }
 }
 
-// 8 independent accumulator tiles per wave, operands never leave registers
-__global__ __launch_bounds__(512) void mfma_probe_kernel(float* sink, int iters)
+// 8 x 8 accumulator tiles of 16 x 16 per wave (the large GEMM tile's register layout), one wave per SIMD;
+// the sixteen operand fragments are read once and never leave registers
+__global__ __launch_bounds__(256) void mfma_probe_kernel(const uint4* __restrict__ operands, float* sink, int iters)
 {
-    bf16x8_t a, b;
+    bf16x8_t a[8], b[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) { a[e] = (__bf16)(0.001f * (float)((threadIdx.x + e) & 15)); b[e] = (__bf16)(0.002f * (float)((threadIdx.x * 3 + e) & 15)); }
-    f32x16_t acc[8];
+    for (int i = 0; i < 8; ++i) {
+        a[i] = __builtin_bit_cast(bf16x8_t, operands[i * 256 + threadIdx.x]);
+        b[i] = __builtin_bit_cast(bf16x8_t, operands[(8 + i) * 256 + threadIdx.x]);
+    }
+    f32x4_t acc[8][8];
 #pragma unroll
-    for (int t = 0; t < 8; ++t)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
-    for (int i = 0; i < iters; ++i) {
+        for (int j = 0; j < 8; ++j)
 #pragma unroll
-        for (int t = 0; t < 8; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[t], 0, 0, 0);
+            for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
     }
     float s = 0.f;
 #pragma unroll
-    for (int t = 0; t < 8; ++t) s += acc[t][0] + acc[t][15];
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) s += acc[i][j][0] + acc[i][j][3];
     if (s == 12345.678f) sink[threadIdx.x] = s;  // keeps the loop alive; never true in practice
 }
 
@@ -58,11 +69,11 @@ hipError_t launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream
     return hipGetLastError();
 }
 
-hipError_t launch_mfma_probe(float* sink, int iters, int workgroups, hipStream_t st)
+hipError_t launch_mfma_probe(const void* operands, float* sink, int iters, int workgroups, hipStream_t st)
 {
     if (iters <= 0 || workgroups <= 0) return hipSuccess;
     TraceScope ts(DORA_K_PROBE_MFMA, st);
-    mfma_probe_kernel<<<dim3(workgroups), dim3(512), 0, st>>>(sink, iters);
+    mfma_probe_kernel<<<dim3(workgroups), dim3(256), 0, st>>>((const uint4*)operands, sink, iters);
     return hipGetLastError();
 }
 

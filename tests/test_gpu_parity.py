@@ -491,7 +491,8 @@ def test_probes_run_and_copy_is_exact():
     D.dora_probe_copy(src, dst, n)
     assert torch.equal(src, dst)
     sink = torch.zeros(512, dtype=torch.float32, device=G.DEV)
-    D.dora_probe_mfma(sink, 4, 8)
+    operands = torch.randn(65536 // 2, device=G.DEV).to(torch.bfloat16)
+    D.dora_probe_mfma(operands, sink, 4, 8)
     torch.cuda.synchronize()
     assert float(sink.abs().max()) == 0.0
 
