@@ -10,17 +10,18 @@
 // Structure (per workgroup): a BM x BN tile of C; K is walked in steps of 64 through rings of LDS
 // buffers that the global loads fill directly (buffer_load ... lds, 16 bytes per lane, no register
 // staging).  A K step of 64 makes every row segment a load instruction fetches a full 128-byte line;
-// 64-byte segments stream at about two thirds of that rate.  v_mfma_f32_32x32x16_bf16 on 64-wide
-// wavefronts, four waves per workgroup, each owning a (BM/2) x (BN/2) sub-tile.  The N-side fragment is fed as the MFMA's first operand so that every lane ends up
-// holding four consecutive n for one m, which makes the epilogue's stores and row-dots
-// vector-friendly.  Workgroup ids are remapped so that each of the 8 XCDs (own L2 each) works on a
-// compact block of tiles, walked in groups of 8 tile-rows.
+// 64-byte segments stream at about two thirds of that rate.  Four 64-wide wavefronts per workgroup,
+// each owning a (BM/2) x (BN/2) sub-tile.  The N-side fragment is fed as the MFMA's first operand so
+// that every lane ends up holding four consecutive n for one m, which makes the epilogue's stores and
+// row-dots vector-friendly.  Workgroup ids are remapped so that each of the 8 XCDs (own L2 each) works
+// on a compact block of tiles, walked in groups of 8 tile-rows.
 //
-// Two tile shapes.  128 x 128 (64 x 64 per wave, two workgroups per CU, which hide each other's
-// stalls) for the skinny products.  256 x 256 (128 x 128 per wave, accumulators in AGPRs, one wave
-// per SIMD, all 160 KB of LDS) for the large ones: the LDS path of a SIMD moves one 16-byte-per-lane
-// fragment read in about the time of one MFMA, and this is the shape with the fewest fragment reads
-// per MFMA; its memory instructions are interleaved with the MFMAs by hand.
+// Two tile shapes.  128 x 128 (64 x 64 per wave as 2 x 2 of v_mfma_f32_32x32x16, two workgroups per CU,
+// which hide each other's stalls) for the skinny products.  256 x 256 (128 x 128 per wave as 8 x 8 of
+// v_mfma_f32_16x16x32, accumulators in AGPRs, one wave per SIMD, all 160 KB of LDS) for the large ones:
+// this is the wave tile with the fewest fragment reads per MFMA, the instruction shape that draws the
+// least power per flop (these launches are power limited), and its memory instructions are interleaved
+// with the MFMAs by hand.
 #include "common.hpp"
 
 #include <type_traits>
