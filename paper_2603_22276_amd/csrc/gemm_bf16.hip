@@ -635,58 +635,68 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
         // 64 x 64 per wave, one workgroup per CU (launches of at most one workgroup per CU get this
         // tile): with a single wave per SIMD and only four MFMAs per k-step, a fragment read issued one
         // k-step ahead has not landed when its MFMAs are due.  Fragments are therefore read two k-steps
-        // ahead into four register sets (one per k-step of a K step), one fragment behind each MFMA,
-        // and the global loads of a K step follow the MFMAs of k-step 2.  The workgroup barrier sits in
-        // the middle of a K step: before k-step 2, whose MFMAs are interleaved with the first reads of
-        // the next K step.  By then every wave has consumed all fragments of the previous K step, so its
-        // buffer is refilled there.
+        // ahead into four register sets (one per k-step of a K step), one fragment behind each MFMA.
+        // The workgroup barrier sits in the middle of a K step: before k-step 2, whose MFMAs are
+        // interleaved with the first reads of the next K step.  By then every wave has consumed all
+        // fragments of the previous K step, so its buffer is refilled from there on: a quarter of a K
+        // step's global loads behind the MFMAs of each of the next four k-steps (k-steps 2, 3 and, past the
+        // end of the loop body, 0 and 1), one load every other MFMA.  (All of them behind one k-step held
+        // the wave up for half a K step's time: loads closer together than about six MFMA slots of 16
+        // cycles wait for one another.)
         constexpr int NM = MT * NT, NF = MT + NT;
         static_assert(KSTEPS == 4 && NF <= NM && LPT % NM == 0, "deep-prefetch schedule assumptions");
         bf16x8_t fa[4][MT], fb[4][NT];
-        // MFMAs of k-step KC (set KC); fragments of k-step KN (set KN) of ring slot `slot`; LOADS: the
-        // global loads of the cursor's K step into ring slot `fill`
-        auto burst = [&](auto kc_tag, auto kn_tag, auto loads_tag, int slot, int fill, int kk) {
-            constexpr int KC = decltype(kc_tag)::value, KN = decltype(kn_tag)::value;
-            constexpr bool LOADS = decltype(loads_tag)::value;
+        // MFMAs of k-step KC (set KC); fragments of k-step KN (set KN) of ring slot `slot`; quarter Q of
+        // the global loads of the cursors' K step into ring slot `fill` (M side first)
+        constexpr int LQ = LPT / 4;
+        static_assert(LPT % 4 == 0 && T::NLA % LQ == 0 && LQ * 2 <= NM, "a quarter of the loads behind every other MFMA");
+        auto burst = [&](auto kc_tag, auto kn_tag, auto q_tag, int slot, int fill, int kk) {
+            constexpr int KC = decltype(kc_tag)::value, KN = decltype(kn_tag)::value, Q = decltype(q_tag)::value;
             const uint32_t sa = smem_lds + T::a_slot_off(slot), sb = smem_lds + T::b_slot_off(slot);
             static_for<NM>([&](auto nt) {
                 constexpr int n = decltype(nt)::value;
                 constexpr int i = n / NT, j = n % NT;
                 acc[i][j] = E::mfma(fb[KC][j], fa[KC][i], acc[i][j]);
                 if constexpr (n < NF) read_frag(kn_tag, nt, fa[KN], fb[KN], sa, sb);
-                if constexpr (LOADS) {
-                    static_for<LPT / NM>([&](auto dt) {
-                        constexpr int t = n * (LPT / NM) + decltype(dt)::value;
-                        if constexpr (t < T::NLA) {
-                            ca.template issue_one<t>(smem + T::a_slot_off(fill), wave);
-                            if constexpr (t == T::NLA - 1) advance_a();
-                        } else {
-                            cb.template issue_one<t - T::NLA>(smem + T::b_slot_off(fill), wave);
-                            if constexpr (t == LPT - 1) advance_b();
-                        }
-                    });
+                if constexpr (n % 2 == 1 && n / 2 < LQ) {
+                    constexpr int t = Q * LQ + n / 2;
+                    if constexpr (t < T::NLA) {
+                        ca.template issue_one<t>(smem + T::a_slot_off(fill), wave);
+                        if constexpr (t == T::NLA - 1) advance_a();
+                    } else {
+                        cb.template issue_one<t - T::NLA>(smem + T::b_slot_off(fill), wave);
+                        if constexpr (t == LPT - 1) advance_b();
+                    }
                 }
                 __builtin_amdgcn_sched_barrier(0);
             });
             base_term(fa[KC], kk);
         };
-        typedef std::true_type Loads;
-        typedef std::false_type NoLoads;
+        // before the loop: steps 0 .. STAGES-3 and the first half of the loads of step STAGES-2
 #pragma unroll
-        for (int u = 0; u < STAGES - 1; ++u) issue(u);
-        wait_vmcnt<(STAGES - 2) * LPT>();              // own share of step 0 landed
+        for (int u = 0; u < STAGES - 2; ++u) issue(u);
+        static_for<LPT / 2>([&](auto tt) {
+            constexpr int t = decltype(tt)::value;
+            if constexpr (t < T::NLA) {
+                ca.template issue_one<t>(smem + T::a_slot_off(STAGES - 2), wave);
+                if constexpr (t == T::NLA - 1) advance_a();
+            } else {
+                cb.template issue_one<t - T::NLA>(smem + T::b_slot_off(STAGES - 2), wave);
+            }
+        });
+        wait_vmcnt<(STAGES - 3) * LPT + LPT / 2>();    // own share of step 0 landed
         __builtin_amdgcn_s_barrier();
         frags(K0{}, fa[0], fb[0], 0);
         frags(K1{}, fa[1], fb[1], 0);
         for (int u = 0; u < nsteps; ++u) {
-            const int slot = u % STAGES, next = (u + 1) % STAGES, fill = (u + STAGES - 1) % STAGES;
-            __builtin_amdgcn_sched_barrier(0);
+            const int slot = u % STAGES, next = (u + 1) % STAGES;
+            const int fill_late = (u + STAGES - 2) % STAGES, fill = (u + STAGES - 1) % STAGES;
             wait_lgkmcnt<FRAG_OPS>();                  // set 0 landed; set 1 may still be in flight
             __builtin_amdgcn_sched_barrier(0);
-            burst(K0{}, K2{}, NoLoads{}, slot, 0, 4 * u);
+            burst(K0{}, K2{}, K2{}, slot, fill_late, 4 * u);        // third quarter of step u + STAGES - 2
             wait_lgkmcnt<FRAG_OPS>();
             __builtin_amdgcn_sched_barrier(0);
-            burst(K1{}, K3{}, NoLoads{}, slot, 0, 4 * u + 1);
+            burst(K1{}, K3{}, K3{}, slot, fill_late, 4 * u + 1);    // its last quarter
             // own share of step u+1 landed (STAGES-3 later steps may be in flight); after the barrier it
             // is visible to all, and the buffer of step u-1, whose last fragments every wave consumed
             // before it got here, takes step u + STAGES - 1
@@ -694,10 +704,10 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
             wait_lgkmcnt<FRAG_OPS>();                  // set 2 landed
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);          // no MFMA may move above the waits
-            burst(K2{}, K0{}, Loads{}, next, fill, 4 * u + 2);
+            burst(K2{}, K0{}, K0{}, next, fill, 4 * u + 2);         // first quarter of step u + STAGES - 1
             wait_lgkmcnt<FRAG_OPS>();
             __builtin_amdgcn_sched_barrier(0);
-            burst(K3{}, K1{}, NoLoads{}, next, 0, 4 * u + 3);
+            burst(K3{}, K1{}, K1{}, next, fill, 4 * u + 3);         // second quarter
         }
         wait_vmcnt<0>();
         wait_lgkmcnt<0>();

@@ -38,6 +38,8 @@ SMALL = [
     I.stress(cfg_bf16("bf16_mid", 1024, 1536, 384, 640, seed=4)),
     cfg_bf16("bf16_mid", 1024, 1536, 384, 640, seed=4),
     cfg_bf16("bf16_bigtile_ragged", 4104, 264, 16, 4104, sigma_B=2e-2, seed=5),
+    # dx = dz W + dh A on the 256 x 256 tile (K-strided N side) with ragged K in both segments and an odd number of K steps
+    cfg_bf16("bf16_bigtile_dx_ragged", 264, 4104, 16, 4104, sigma_B=2e-2, seed=6),
     # few tiles and a long K: h = x A^T (first) and dh = s dz B (second) run split along K with a fixed-order reduce
     cfg_bf16("bf16_splitk_h", 264, 2312, 40, 300, seed=8),
     cfg_bf16("bf16_splitk_dh", 3080, 264, 24, 200, sigma_B=2e-2, seed=9),
