@@ -730,8 +730,26 @@ __global__ __launch_bounds__(T::THREADS) void gemm_bf16_kernel(GemmPair grp)
             __builtin_amdgcn_sched_barrier(0);          // no MFMA may move above the waits
             frags(K0{}, a0, b0, slot);
             __builtin_amdgcn_sched_barrier(0);
-            issue((u + STAGES - 1) % STAGES);
-            if (u > 0) mma(a1, b1, KSTEPS * u - 1);      // its fragments were complete before the barrier
+            if (u > 0) {
+                // the last MFMAs of the previous step (their fragments were complete before the barrier) with
+                // the loads of step u + STAGES - 1 behind them, a share behind each
+                const int fill = (u + STAGES - 1) % STAGES;
+                static_for<MT * NT>([&](auto nt) {
+                    constexpr int n = decltype(nt)::value, i = n / NT, j = n % NT;
+                    acc[i][j] = E::mfma(b1[j], a1[i], acc[i][j]);
+                    static_for<LPT / (MT * NT)>([&](auto dt) {
+                        constexpr int t = n * (LPT / (MT * NT)) + decltype(dt)::value;
+                        if constexpr (t < T::NLA) ca.template issue_one<t>(smem + T::a_slot_off(fill), wave);
+                        else cb.template issue_one<t - T::NLA>(smem + T::b_slot_off(fill), wave);
+                    });
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+                base_term(a1, KSTEPS * u - 1);
+                advance_a();
+                advance_b();
+            } else {
+                issue((u + STAGES - 1) % STAGES);
+            }
             __builtin_amdgcn_sched_barrier(0);
             static_for<KSTEPS / 2>([&](auto qt) {
                 constexpr int q = decltype(qt)::value;
