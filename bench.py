@@ -144,17 +144,21 @@ class ResidentModule:
                                       [D.PHASE_BACKWARD if mode == "fwd_bwd_saved" else D.PHASE_BACKWARD_RECOMPUTE])
         self.ws_bytes = max(D.dora_workspace_bytes(self.desc, p) for p in phases)
         self.ws = None  # set by the workload: one workspace shared by all modules
+        # recompute mode only: keep the [d_out] row norm of the forward for the backward (4 bytes per output row)
+        # instead of rebuilding it there
+        self.carry_norm = False
 
     def forward(self, fwd_fn=None):
         (fwd_fn or self.fwd_fn)(self.desc, self.x, self.W, self.A, self.B, self.m, None, None, self.y, self.h, self.inner,
-                                self.c if self.mode == "fwd_bwd_saved" else None, self.ws)
+                                self.c if (self.mode == "fwd_bwd_saved" or self.carry_norm) else None, self.ws)
 
     def backward(self):
         if self.mode == "fwd_bwd_saved":
             self.D.dora_backward(self.desc, self.dy, self.x, self.W, self.A, self.B, self.m, self.c, self.h, self.inner,
                                  self.dx, self.dA, self.dB, self.dm, self.ws)
         elif self.mode == "fwd_bwd_recompute":
-            self.D.dora_backward(self.desc, self.dy, self.x, self.W, self.A, self.B, self.m, None, None, None,
+            self.D.dora_backward(self.desc, self.dy, self.x, self.W, self.A, self.B, self.m,
+                                 self.c if self.carry_norm else None, None, None,
                                  self.dx, self.dA, self.dB, self.dm, self.ws)
 
 
@@ -497,6 +501,26 @@ def measure(wl, args, torch, D, extras):
     return out
 
 
+def recompute_extras(args, torch):
+    """Beside `value` for the recompute workloads (C4, C5): the same step with each module's [d_out] row norm kept
+    from its forward and handed to its backward, which then recomputes h and inner but not the norm."""
+    def extras(wl, ms_untraced):
+        for m in wl.modules:
+            m.carry_norm = True
+        for _ in range(2):
+            wl.step()
+        ms, _ = time_steps(torch, wl.step, args.steps)
+        for m in wl.modules:
+            m.carry_norm = False
+        return {"row_norm_carried_to_backward": {
+            "ms_per_step_without_event_pairs": ms, "tokens_per_s": wl.tokens / (ms * 1e-3),
+            "against_ms_per_step_without_event_pairs": ms_untraced,
+            "note": "the norm is rank and batch independent within a step: a caller that keeps the fp32 [d_out] vector "
+                    "w_norm_out of dora_forward and passes it to dora_backward skips the second norm of the step; "
+                    "`value` recomputes it, as the workload is defined"}}
+    return extras
+
+
 def c3_extras(args, torch, D, G):
     """Figures reported beside `value` for the single bf16 modules: the step as a HIP graph, the other forward
     path, and what this card sustains on a plain copy and a register-resident MFMA loop."""
@@ -626,7 +650,9 @@ def main():
         phase = {"C1": "fwd", "C2": "fwd", "C3": "fwd+bwd", "C4": "fwd+recompute+bwd"}[args.config]
         out = {"metric": METRIC_FMT.format(phase=phase, d_in=cfg.d_in if args.config != "C4" else "5120/27648", r=cfg.r,
                                            dtype="bf16" if cfg.dtype == "bf16" else "fp32")}
-        out.update(measure(wl, args, torch, D, c3_extras(args, torch, D, G) if args.config in ("C2", "C3") else None))
+        extras = (c3_extras(args, torch, D, G) if args.config in ("C2", "C3")
+                  else recompute_extras(args, torch) if args.config == "C4" else None)
+        out.update(measure(wl, args, torch, D, extras))
         out.update({"dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
                     "config": {"workload": wl.name, "tokens": wl.tokens, "phase": wl.phase_text,
                                "modules": [{"d_out": m.cfg.d_out, "d_in": m.cfg.d_in, "r": m.cfg.r} for m in wl.modules],
@@ -642,7 +668,7 @@ def main():
     per_rank, cpu = {}, None
     for rank in ranks:
         wl, samples, note = build_workload("C5", args, torch, D, G, I, rank=rank)
-        res = measure(wl, args, torch, D, None)
+        res = measure(wl, args, torch, D, recompute_extras(args, torch))
         res["config"] = {"workload": wl.name, "tokens": wl.tokens, "phase": wl.phase_text, "r": rank,
                          "modules_resident": len(wl.modules)}
         per_rank[rank] = res
