@@ -18,7 +18,7 @@ TOL = {"bf16": {"norm": 1e-3, "tensor": 2e-2}, "f16": {"norm": 1e-3, "tensor": 5
 
 
 # Achieved errors of the run, keyed by "<context>/<tensor>": written to $DORA_PARITY_LOG at exit when that
-# variable is set (the figures quoted in the design doc come from such a run).
+# variable is set (the achieved-error table of the design notes comes from such a run).
 ACHIEVED = {}
 CONTEXT = [""]
 
